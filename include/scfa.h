@@ -1,0 +1,258 @@
+/*
+ * scfa.h -- C ABI of the Sparse Causal Flash Attention library for MI355X (gfx950).
+ *
+ * The library computes exact causal softmax attention restricted to a dynamic
+ * sparsity pattern (paper Sec. 3), in two variants:
+ *   - hash-sparse (Sec. 3.2): query i may attend key j iff j <= i and
+ *     bucket_q[i] == bucket_k[j];
+ *   - QK-sparse / QK-dropping (Sec. 3.1): iff j <= i and both are kept.
+ * A query with no allowed key outputs a zero vector (Sec. 3.1, "Edge cases");
+ * its logsumexp is -inf.
+ *
+ * Pipeline (one (batch, head) pair is a "segment"; S = B*H segments):
+ *   scfa_sort_by_bucket / scfa_compact_keep   stable permutation, original-index vectors
+ *   scfa_gather_rows                          permuted / compacted Q, K, V
+ *   scfa_block_ranges                         tile-skip schedule (work lists)
+ *   scfa_hash_attn_fwd / scfa_qkdrop_attn_fwd O and logsumexp, written in ORIGINAL order
+ *   scfa_hash_attn_bwd / scfa_qkdrop_attn_bwd dQ, dK, dV, written in ORIGINAL order
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless it is marked "host".
+ *   - Tensors are contiguous: Q/K/V/O/dO [B,H,T,d] (= [S,T,d]); per-token
+ *     vectors [B,H,T] (= [S,T]).  T_Q == T_KV == T.
+ *   - The caller owns every buffer.  The library never allocates or frees
+ *     device memory and never synchronises: all work is enqueued on `stream`
+ *     (a hipStream_t passed as void*; NULL is the default stream).
+ *   - Outputs are fully written (zeros for dropped / stranded rows); callers
+ *     need not clear them.
+ *   - Every function returns SCFA_OK or a negative error code; nothing is
+ *     launched when an argument check fails.  No function throws or aborts.
+ *   - `flags` is reserved and must be 0.
+ */
+#ifndef SCFA_H
+#define SCFA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SCFA_OK            0
+#define SCFA_EINVAL       (-1)  /* null pointer, non-positive size, bad alignment, bad value */
+#define SCFA_EUNSUPPORTED (-2)  /* dtype / head dim / nb / tile size outside the built set */
+#define SCFA_EWORKSPACE   (-3)  /* workspace too small */
+#define SCFA_EHIP         (-4)  /* a HIP runtime call failed; see scfa_last_hip_error() */
+
+#define SCFA_BF16 0             /* 16-bit brain float, fp32 accumulation */
+#define SCFA_F32  1             /* fp32 (forward only) */
+
+#define SCFA_HASH   0
+#define SCFA_QKDROP 1
+
+#define SCFA_MAX_BUCKETS 256
+#define SCFA_WORK_STRIDE 8      /* int32 words per work item */
+
+/* Library version (major*10000 + minor*100 + patch). */
+int scfa_version(void);
+
+/* hipError_t value of the last failed HIP call made by this library on the
+ * calling thread (0 if none). */
+int scfa_last_hip_error(void);
+
+/* Human-readable name of an SCFA_* error code (static string, host). */
+const char *scfa_error_string(int code);
+
+/* ------------------------------------------------------------------------
+ * a1. Stable sort of token positions by bucket id, per segment (Sec. 3.2:
+ * "reorder Q, K, V by sorting them along the sequence length dimension"; the
+ * sort must be stable so that original positions stay increasing inside a
+ * bucket).
+ *
+ *   bucket             [S,T] int32, 0 <= bucket < nb (ids outside the range are
+ *                      clamped into it so the call stays memory-safe)
+ *   idx_out            [S,T] int32: idx_out[s,r] = original position of sorted row r;
+ *                      (bucket[idx[r]], idx[r]) is lexicographically increasing
+ *   bucket_sorted_out  [S,T] int32 (nullable): bucket id of sorted row r
+ *   bucket_off_out     [S,nb+1] int32: off[s,b] = number of tokens with id < b
+ * Limits: 1 <= nb <= SCFA_MAX_BUCKETS, 1 <= T, 1 <= S.
+ */
+int scfa_sort_by_bucket(const int32_t *bucket, int S, int T, int nb,
+                        int32_t *idx_out, int32_t *bucket_sorted_out,
+                        int32_t *bucket_off_out, void *stream);
+
+/* ------------------------------------------------------------------------
+ * a2. Compaction for QK-dropping (Sec. 3.1, "Shrinking the attention matrix").
+ *
+ *   keep       [S,T] uint8, non-zero = kept
+ *   idx_out    [S,T] int32: first count[s] entries = kept positions, increasing;
+ *              the remaining entries = dropped positions, increasing (the order a
+ *              stable descending sort of the keep flag gives)
+ *   count_out  [S] int32: number of kept tokens
+ */
+int scfa_compact_keep(const uint8_t *keep, int S, int T,
+                      int32_t *idx_out, int32_t *count_out, void *stream);
+
+/* ------------------------------------------------------------------------
+ * a3. Row gather: out[s,r,:] = x[s, idx[s,r], :] for r < n[s], where n[s] =
+ * count[s] if `count` is non-null, else T.  Rows r >= n[s] of `out` are not
+ * touched.  `out` has the same [S,T,d] capacity as `x` (Sec. 3: the permuted /
+ * compacted Q, K, V the kernels consume).  x and out must be 16-byte aligned
+ * and must not overlap.  dtype: SCFA_BF16 or SCFA_F32; d*sizeof(elem) must be a
+ * multiple of 16.
+ */
+int scfa_gather_rows(const void *x, const int32_t *idx, const int32_t *count,
+                     int S, int T, int d, int dtype, void *out, void *stream);
+
+/* ------------------------------------------------------------------------
+ * a4. Tile-skip schedule.  The paper finds, per block of queries, the range of
+ * key blocks that can hold an allowed pair (Sec. 3.1 j_stop; Sec. 3.2 j_start,
+ * j_stop and its causal refinement).  This library owns its tiling, so it
+ * anchors tiles at bucket boundaries: every work item covers query rows of ONE
+ * bucket and the keys of that same bucket, so the bucket test is structural
+ * and only the causal test on original positions remains inside a tile.
+ *
+ * Tile sizes must be the ones scfa_tile_config() reports for (d, dtype).
+ *
+ *   variant     SCFA_HASH: q_off/k_off are the [S,nb+1] offsets of
+ *               scfa_sort_by_bucket.  SCFA_QKDROP: nb must be 1 and q_off/k_off
+ *               are the [S] kept counts of scfa_compact_keep.
+ *   q_idx,k_idx [S,T] original positions of the permuted rows
+ *
+ *   fwd_work_out [S, n_fwd, 8] int32, n_fwd = scfa_num_work_items(T, nb, fwd_tile_m).
+ *     Item = { q_begin, q_count, k_begin, k_count, k_nomask, bucket, 0, 0 }:
+ *     permuted query rows [q_begin, q_begin+q_count) attend permuted key rows
+ *     [k_begin, k_begin+k_count): the keys of the same bucket whose position is
+ *     <= the LARGEST query position of the item.  The first k_nomask of these
+ *     keys have a position <= the SMALLEST query position: no mask needed.
+ *     Items of a segment are ordered by decreasing k_count; unused trailing
+ *     items have q_count == 0.
+ *   bwd_work_out [S, n_bwd, 8] int32 (nullable), n_bwd = scfa_num_work_items(T, nb, bwd_tile_n).
+ *     Item = { k_begin, k_count, q_begin, q_count, q_masked, bucket, 0, 0 }:
+ *     permuted key rows [k_begin, k_begin+k_count) are attended by permuted
+ *     query rows [q_begin, q_begin+q_count): the queries of the same bucket
+ *     whose position is >= the SMALLEST key position of the item.  Only the
+ *     first q_masked of them (position < the LARGEST key position) need a mask.
+ *     Ordered by decreasing q_count.
+ *   counters_out [S,4] int64 (nullable): { forward tiles of fwd_tile_m x fwd_tile_n,
+ *     sum of q_count*k_count, backward tiles of bwd_tile_m x bwd_tile_n, sum of
+ *     k_count*q_count } -- the "computed tile" counts throughput is quoted on.
+ */
+int scfa_block_ranges(int variant, const int32_t *q_idx, const int32_t *k_idx,
+                      const int32_t *q_off, const int32_t *k_off,
+                      int S, int T, int nb,
+                      int fwd_tile_m, int fwd_tile_n, int bwd_tile_n, int bwd_tile_m,
+                      int flags,
+                      int32_t *fwd_work_out, int32_t *bwd_work_out,
+                      int64_t *counters_out, void *stream);
+
+/* Number of work items per segment for a tiling of `tile` rows: ceil(T/tile) + nb
+ * (an upper bound of sum_b ceil(n_b/tile)).  Host arithmetic only. */
+int scfa_num_work_items(int T, int nb, int tile);
+
+/* Tile sizes the attention kernels are built for (host out-pointers).
+ * Returns SCFA_EUNSUPPORTED for an unsupported (d, dtype). */
+int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
+                     int *bwd_tile_n, int *bwd_tile_m);
+
+/* ------------------------------------------------------------------------
+ * a5 (+a8). Forward attention over the scheduled tiles (Sec. 3.1 / 3.2; the
+ * per-tile work of Alg. 1 / Alg. 2: scores, causal mask on original positions,
+ * online softmax with the NaN-safe handling of fully masked rows, P.V).
+ *
+ *   q_perm,k_perm,v_perm  [S,T,d] rows in sorted (hash) or compacted (qkdrop) order
+ *   q_idx,k_idx           [S,T] original positions of those rows
+ *   fwd_work, n_fwd       work list of scfa_block_ranges
+ *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d))
+ *   o_out                 [B,H,T,d] in ORIGINAL order, dtype of the inputs
+ *   lse_out               [B,H,T] float, ORIGINAL order: natural-log logsumexp of the
+ *                         scaled scores over allowed keys; -inf for a row with none
+ *   o_f32_out             [B,H,T,d] float (nullable, SCFA_BF16 only): the same O before its
+ *                         rounding to bf16, for the backward's D = <dO, O>; pass it to the
+ *                         backward as o_f32.  Rows of dropped queries are not written.
+ * d: 64 or 128.  SCFA_BF16: scores are bf16 x bf16 products accumulated in fp32; P is
+ * rounded to fp16 and V converted to fp16 (exact for |v| in [2^-14, 65504]) for P.V.
+ *
+ * scfa_qkdrop_attn_fwd additionally takes the kept-query counts n_q [S] and
+ * writes zeros / -inf for the dropped query rows idx[n_q[s] .. T).
+ */
+int scfa_hash_attn_fwd(const void *q_perm, const void *k_perm, const void *v_perm,
+                       const int32_t *q_idx, const int32_t *k_idx,
+                       const int32_t *fwd_work, int n_fwd,
+                       int B, int H, int T, int d, int dtype, float sm_scale, int flags,
+                       void *o_out, float *lse_out, float *o_f32_out, void *stream);
+
+int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
+                         const int32_t *q_idx, const int32_t *k_idx, const int32_t *n_q,
+                         const int32_t *fwd_work, int n_fwd,
+                         int B, int H, int T, int d, int dtype, float sm_scale, int flags,
+                         void *o_out, float *lse_out, float *o_f32_out, void *stream);
+
+/* ------------------------------------------------------------------------
+ * a6 + a7 (+a8). Backward.  The paper states the backward is adapted like the
+ * forward (Sec. 3.1, 3.2: iterate over query blocks per key block); the
+ * gradients are those of the masked softmax attention:
+ *   D_i = <dO_i, O_i>, P_ij = exp(tau s_ij - LSE_i), dS_ij = P_ij (<dO_i,V_j> - D_i),
+ *   dQ_i = tau sum_j dS_ij K_j,  dK_j = tau sum_i dS_ij Q_i,  dV_j = sum_i P_ij dO_i.
+ *
+ *   o, lse        outputs of the forward (ORIGINAL order)
+ *   o_f32         (nullable) the forward's o_f32_out; when given, D is computed from it
+ *                 instead of the bf16-rounded o (tighter gradients), and o may be NULL
+ *   d_o           [B,H,T,d] upstream gradient, ORIGINAL order, dtype of the inputs
+ *   dq_out, dk_out, dv_out   [B,H,T,d] FLOAT32, ORIGINAL order; rows of dropped or
+ *                 stranded queries (dQ) and of dropped or never-attended keys
+ *                 (dK, dV) are written as zeros
+ *   ws, ws_bytes  scratch of at least scfa_attn_bwd_workspace_bytes(S,T,d,dtype),
+ *                 256-byte aligned; contents are undefined afterwards
+ * dtype: SCFA_BF16 only.
+ *
+ * scfa_qkdrop_attn_bwd additionally takes n_q, n_k [S] (kept counts).
+ */
+size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype);
+
+int scfa_hash_attn_bwd(const void *q_perm, const void *k_perm, const void *v_perm,
+                       const int32_t *q_idx, const int32_t *k_idx,
+                       const int32_t *fwd_work, int n_fwd,
+                       const int32_t *bwd_work, int n_bwd,
+                       const void *o, const float *o_f32, const float *lse, const void *d_o,
+                       int B, int H, int T, int d, int dtype, float sm_scale, int flags,
+                       float *dq_out, float *dk_out, float *dv_out,
+                       void *ws, size_t ws_bytes, void *stream);
+
+int scfa_qkdrop_attn_bwd(const void *q_c, const void *k_c, const void *v_c,
+                         const int32_t *q_idx, const int32_t *k_idx,
+                         const int32_t *n_q, const int32_t *n_k,
+                         const int32_t *fwd_work, int n_fwd,
+                         const int32_t *bwd_work, int n_bwd,
+                         const void *o, const float *o_f32, const float *lse, const void *d_o,
+                         int B, int H, int T, int d, int dtype, float sm_scale, int flags,
+                         float *dq_out, float *dk_out, float *dv_out,
+                         void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------------
+ * Per-kernel timing with HIP events on the caller's stream (measurement aid).
+ * While enabled, every kernel launch of the library is bracketed by two
+ * events.  scfa_prof_read synchronises on the recorded events.
+ *   kernel ids: see SCFA_K_* below.
+ */
+#define SCFA_K_SORT        0
+#define SCFA_K_COMPACT     1
+#define SCFA_K_GATHER      2
+#define SCFA_K_RANGES      3
+#define SCFA_K_FWD         4
+#define SCFA_K_BWD_PREP    5
+#define SCFA_K_BWD_DKDV    6
+#define SCFA_K_BWD_DQ      7
+#define SCFA_K_FILL        8
+#define SCFA_K_COUNT       9
+
+int scfa_prof_enable(int on);      /* returns the previous state */
+int scfa_prof_reset(void);
+/* total_ms / launches (host out-pointers) accumulated since the last reset */
+int scfa_prof_read(int kernel_id, double *total_ms, int *launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCFA_H */

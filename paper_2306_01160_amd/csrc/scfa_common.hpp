@@ -1,0 +1,82 @@
+// Shared declarations of the HIP sources of the SCFA library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scfa.h"
+
+namespace scfa {
+
+// ---- error plumbing ---------------------------------------------------------
+extern thread_local int g_last_hip_error;
+
+inline int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return SCFA_EHIP;
+}
+
+#define SCFA_HIP_TRY(expr)                                 \
+    do {                                                   \
+        hipError_t _e = (expr);                            \
+        if (_e != hipSuccess) return ::scfa::hip_fail(_e); \
+    } while (0)
+
+// ---- profiling hooks (scfa_prof_*) -----------------------------------------
+struct ProfScope {
+    int kid;
+    hipStream_t stream;
+    int slot;
+    ProfScope(int kernel_id, hipStream_t s);
+    ~ProfScope();
+};
+
+// ---- work list layout (see scfa_block_ranges) -------------------------------
+constexpr int WORK_STRIDE = SCFA_WORK_STRIDE;
+
+// forward / dQ items
+constexpr int W_QBEGIN = 0, W_QCOUNT = 1, W_KBEGIN = 2, W_KCOUNT = 3, W_KNOMASK = 4, W_BUCKET = 5;
+// backward (key-major) items
+constexpr int BW_KBEGIN = 0, BW_KCOUNT = 1, BW_QBEGIN = 2, BW_QCOUNT = 3, BW_QMASKED = 4;
+
+// ---- tile configuration -------------------------------------------------------
+constexpr int FWD_TILE_M = 128;  // query rows per workgroup (4 waves x 32)
+constexpr int FWD_TILE_N = 64;   // keys per inner step
+constexpr int BWD_TILE_N = 128;  // key rows per workgroup in the dK/dV kernel (4 waves x 32)
+constexpr int BWD_TILE_M = 64;   // query rows per inner step of the dK/dV kernel
+constexpr int F32_TILE_M = 64;   // fp32 path: one thread per query row
+constexpr int F32_TILE_N = 32;
+
+// ---- kernel launchers (defined in the .hip files) ---------------------------
+int launch_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
+                          int32_t* bucket_sorted_out, int32_t* off_out, hipStream_t st);
+int launch_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out,
+                        hipStream_t st);
+int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
+                       int row_bytes, void* out, hipStream_t st);
+int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
+                        const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
+                        int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
+                        int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st);
+int launch_zero_rows(const int32_t* idx, const int32_t* count, int S, int T, int row_bytes,
+                     void* out0, void* out1, float* vec, float vec_value, hipStream_t st);
+int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const int32_t* q_idx,
+                        const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+                        float tau, float* o, float* lse, hipStream_t st);
+int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
+                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+                         float tau, void* o, float* lse, float* o_f32, hipStream_t st);
+int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
+                         int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
+                         hipStream_t st);
+int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
+                              const float* lse_perm, const float* delta_perm, const int32_t* q_idx,
+                              const int32_t* k_idx, const int32_t* bwd_work, int n_bwd, int S, int T,
+                              int d, float tau, float* dk, float* dv, hipStream_t st);
+int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
+                            const float* lse_perm, const float* delta_perm, const int32_t* q_idx,
+                            const int32_t* k_idx, const int32_t* fwd_work, int n_fwd, int S, int T,
+                            int d, float tau, float* dq, hipStream_t st);
+
+}  // namespace scfa

@@ -1,0 +1,204 @@
+// Integer / data-movement passes: stable sort by bucket, compaction of kept tokens,
+// row gather, zero-fill of dropped rows.  All bit-exact; HBM- or latency-bound.
+//
+// Sort (paper Sec. 3.2) and compaction (Sec. 3.1) are the same operation: a stable
+// counting sort of the positions 0..T-1 by a small key (bucket id, or "dropped" flag).
+// One workgroup of 16 wavefronts owns one (batch, head) segment: every wavefront
+// histograms a contiguous run of the sequence, the per-(key, wavefront) counts are
+// turned into start offsets in (key, wavefront) order, and every wavefront then ranks
+// its run 64 tokens at a time with wave-wide ballots -- tokens keep their relative
+// order inside a key, which is what makes the sort stable.
+#include "scfa_common.hpp"
+
+namespace scfa {
+
+constexpr int SORT_WAVES = 16;
+constexpr int SORT_THREADS = SORT_WAVES * 64;
+
+template <bool KEEP_MODE>
+__device__ __forceinline__ int load_key(const void* keys, size_t i, int nb)
+{
+    if (KEEP_MODE) {
+        return reinterpret_cast<const uint8_t*>(keys)[i] != 0 ? 0 : 1;
+    } else {
+        int k = reinterpret_cast<const int32_t*>(keys)[i];
+        k = k < 0 ? 0 : k;
+        return k >= nb ? nb - 1 : k;
+    }
+}
+
+// keys: [S,T] int32 bucket ids, or uint8 keep flags in KEEP_MODE (key 0 = kept, 1 = dropped).
+// off_out: [S,nb+1] in bucket mode; [S] kept count in KEEP_MODE.
+template <bool KEEP_MODE>
+__global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
+    const void* __restrict__ keys, int T, int nb, int nbits, int32_t* __restrict__ idx_out,
+    int32_t* __restrict__ key_sorted_out, int32_t* __restrict__ off_out)
+{
+    extern __shared__ int32_t smem[];
+    int32_t* hist = smem;                       // [SORT_WAVES][nb]  counts, then running bases
+    int32_t* tot = smem + SORT_WAVES * nb;      // [nb+1]
+    const int s = blockIdx.x;
+    const int wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const size_t seg = (size_t)s * T;
+
+    // contiguous run of this wavefront, a multiple of 64 tokens
+    int run = (T + SORT_WAVES - 1) / SORT_WAVES;
+    run = (run + 63) & ~63;
+    const int r0 = min(wave * run, T);
+    const int r1 = min(r0 + run, T);
+
+    for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] = 0;
+    __syncthreads();
+    for (int t = r0 + lane; t < r1; t += 64) atomicAdd(&hist[wave * nb + load_key<KEEP_MODE>(keys, seg + t, nb)], 1);
+    __syncthreads();
+
+    // per key: exclusive prefix over wavefronts (in place) and the key total
+    for (int k = threadIdx.x; k < nb; k += SORT_THREADS) {
+        int acc = 0;
+        for (int w = 0; w < SORT_WAVES; ++w) {
+            const int c = hist[w * nb + k];
+            hist[w * nb + k] = acc;
+            acc += c;
+        }
+        tot[k] = acc;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {   // exclusive prefix over keys (nb <= 256)
+        int acc = 0;
+        for (int k = 0; k < nb; ++k) {
+            const int c = tot[k];
+            tot[k] = acc;
+            acc += c;
+        }
+        tot[nb] = acc;
+    }
+    __syncthreads();
+    if (KEEP_MODE) {
+        if (threadIdx.x == 0) off_out[s] = tot[1];
+    } else {
+        for (int k = threadIdx.x; k <= nb; k += SORT_THREADS) off_out[(size_t)s * (nb + 1) + k] = tot[k];
+    }
+    for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] += tot[i % nb];
+    __syncthreads();
+
+    // rank and scatter, 64 consecutive tokens per step
+    int32_t* base = hist + wave * nb;
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    for (int t0 = r0; t0 < r1; t0 += 64) {
+        const int t = t0 + lane;
+        const bool valid = t < r1;
+        const int key = valid ? load_key<KEEP_MODE>(keys, seg + t, nb) : 0;
+        unsigned long long same = __ballot(valid);
+        for (int b = 0; b < nbits; ++b) {
+            const bool bit = (key >> b) & 1;
+            const unsigned long long m = __ballot(bit);
+            same &= bit ? m : ~m;
+        }
+        const int rank = __popcll(same & lt_mask);
+        const int cnt = __popcll(same);
+        int pos = 0;
+        if (valid) pos = base[key] + rank;
+        __builtin_amdgcn_wave_barrier();
+        if (valid && rank == 0) base[key] += cnt;
+        __builtin_amdgcn_wave_barrier();
+        if (valid) {
+            idx_out[seg + pos] = t;
+            if (key_sorted_out) key_sorted_out[seg + pos] = key;
+        }
+    }
+}
+
+int launch_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
+                          int32_t* bucket_sorted_out, int32_t* off_out, hipStream_t st)
+{
+    int nbits = 0;
+    while ((1 << nbits) < nb) ++nbits;
+    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
+    ProfScope prof(SCFA_K_SORT, st);
+    hipLaunchKernelGGL(stable_sort_small_keys_kernel<false>, dim3(S), dim3(SORT_THREADS), smem, st,
+                       bucket, T, nb, nbits, idx_out, bucket_sorted_out, off_out);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+int launch_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out,
+                        hipStream_t st)
+{
+    const int nb = 2;
+    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
+    ProfScope prof(SCFA_K_COMPACT, st);
+    hipLaunchKernelGGL(stable_sort_small_keys_kernel<true>, dim3(S), dim3(SORT_THREADS), smem, st,
+                       keep, T, nb, 1, idx_out, (int32_t*)nullptr, count_out);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Row gather: 16 bytes per thread, a row of d elements is row_bytes/16 consecutive
+// lanes, so every row is read and written as whole cache lines.
+__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x,
+                                                          const int32_t* __restrict__ idx,
+                                                          const int32_t* __restrict__ count, int T,
+                                                          int chunks_per_row, uint4* __restrict__ out)
+{
+    const int s = blockIdx.y;
+    const int n = count ? count[s] : T;
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int r = (int)(g / chunks_per_row);
+    const int c = (int)(g % chunks_per_row);
+    if (r >= n) return;
+    const int src = idx[(size_t)s * T + r];
+    out[((size_t)s * T + r) * chunks_per_row + c] = x[((size_t)s * T + src) * chunks_per_row + c];
+}
+
+int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
+                       int row_bytes, void* out, hipStream_t st)
+{
+    const int cpr = row_bytes / 16;
+    const long long total = (long long)T * cpr;
+    dim3 grid((unsigned)((total + 255) / 256), S);
+    ProfScope prof(SCFA_K_GATHER, st);
+    hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, st, (const uint4*)x, idx, count, T, cpr,
+                       (uint4*)out);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Zero the rows idx[s, count[s] .. T) of up to two [S,T,row] outputs (original order)
+// and set vec[s, idx] = vec_value: the dropped queries / keys of QK-dropping.
+__global__ __launch_bounds__(256) void zero_rows_kernel(const int32_t* __restrict__ idx,
+                                                        const int32_t* __restrict__ count, int T,
+                                                        int chunks_per_row, uint4* __restrict__ out0,
+                                                        uint4* __restrict__ out1,
+                                                        float* __restrict__ vec, float vec_value)
+{
+    const int s = blockIdx.y;
+    const int n = count[s];
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int r = n + (int)(g / chunks_per_row);
+    const int c = (int)(g % chunks_per_row);
+    if (r >= T) return;
+    const int dst = idx[(size_t)s * T + r];
+    const uint4 z = make_uint4(0u, 0u, 0u, 0u);
+    const size_t o = ((size_t)s * T + dst) * chunks_per_row + c;
+    if (out0) out0[o] = z;
+    if (out1) out1[o] = z;
+    if (vec && c == 0) vec[(size_t)s * T + dst] = vec_value;
+}
+
+int launch_zero_rows(const int32_t* idx, const int32_t* count, int S, int T, int row_bytes,
+                     void* out0, void* out1, float* vec, float vec_value, hipStream_t st)
+{
+    const int cpr = row_bytes / 16;
+    const long long total = (long long)T * cpr;
+    dim3 grid((unsigned)((total + 255) / 256), S);
+    ProfScope prof(SCFA_K_FILL, st);
+    hipLaunchKernelGGL(zero_rows_kernel, grid, dim3(256), 0, st, idx, count, T, cpr, (uint4*)out0,
+                       (uint4*)out1, vec, vec_value);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+}  // namespace scfa

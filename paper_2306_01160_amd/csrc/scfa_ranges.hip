@@ -1,0 +1,187 @@
+// Tile-skip schedule (paper Sec. 3.1: j_stop from the key / query index vectors;
+// Sec. 3.2: j_start, j_stop from the bucket ids, then the causal refinement).
+//
+// The paper's kernels scan blocks of the index vectors inside every program.  Here
+// the schedule is a pass of its own, and because this library owns the tiling it
+// anchors tiles at bucket boundaries: a work item is a tile of query rows of ONE
+// bucket together with the range of keys of the same bucket that the causal test
+// can let through.  Positions are increasing inside a bucket (stable sort), so both
+// range ends are binary searches in the key (query) index vector:
+//   forward item : keys with position <= largest query position of the tile
+//                  (and the prefix with position <= smallest query position needs no mask)
+//   backward item: queries with position >= smallest key position of the tile
+//                  (only those with position < largest key position need a mask)
+// Items of a segment are emitted in order of decreasing work so that the long
+// ones are dispatched first.
+#include "scfa_common.hpp"
+
+namespace scfa {
+
+constexpr int RANGES_THREADS = 256;
+
+// number of entries of a[0..n) that are <= v (a increasing)
+__device__ __forceinline__ int count_le(const int32_t* __restrict__ a, int n, int v)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] <= v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+// number of entries of a[0..n) that are < v
+__device__ __forceinline__ int count_lt(const int32_t* __restrict__ a, int n, int v)
+{
+    int lo = 0, hi = n;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] < v) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket; };
+
+// Builds one work list.  "a" is the tiled side (queries forward, keys backward),
+// "b" the ranged side.
+//   FORWARD : b range = keys with pos <= max a pos;  extra = #keys with pos <= min a pos
+//   BACKWARD: b range = queries with pos >= min a pos; extra = #queries of the range with pos < max a pos
+template <bool FORWARD>
+__device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* __restrict__ b_idx,
+                           const int32_t* a_off, const int32_t* b_off, int nb, int tile_a,
+                           int tile_b, int n_items_max, int32_t* __restrict__ work_out,
+                           long long* counters2, int32_t* s_tile_base, int32_t* s_cost)
+{
+    // tiles per bucket -> exclusive prefix (nb <= 256)
+    if (threadIdx.x == 0) {
+        int acc = 0;
+        for (int b = 0; b < nb; ++b) {
+            s_tile_base[b] = acc;
+            acc += (a_off[b + 1] - a_off[b] + tile_a - 1) / tile_a;
+        }
+        s_tile_base[nb] = acc;
+    }
+    __syncthreads();
+    const int n_items = s_tile_base[nb];
+
+    auto make_item = [&](int w) -> Item {
+        // bucket of item w: last b with tile_base[b] <= w
+        int lo = 0, hi = nb - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_tile_base[mid] <= w) lo = mid; else hi = mid - 1;
+        }
+        const int b = lo;
+        Item it;
+        it.bucket = b;
+        it.a_begin = a_off[b] + (w - s_tile_base[b]) * tile_a;
+        it.a_count = min(tile_a, a_off[b + 1] - it.a_begin);
+        const int pos_min = a_idx[it.a_begin];
+        const int pos_max = a_idx[it.a_begin + it.a_count - 1];
+        const int bb = b_off[b], bn = b_off[b + 1] - b_off[b];
+        if (FORWARD) {
+            it.b_begin = bb;
+            it.b_count = count_le(b_idx + bb, bn, pos_max);
+            it.b_extra = count_le(b_idx + bb, bn, pos_min);
+        } else {
+            const int first = count_lt(b_idx + bb, bn, pos_min);
+            it.b_begin = bb + first;
+            it.b_count = bn - first;
+            it.b_extra = count_lt(b_idx + bb, bn, pos_max) - first;
+        }
+        return it;
+    };
+
+    for (int w = threadIdx.x; w < n_items; w += RANGES_THREADS) s_cost[w] = make_item(w).b_count;
+    __syncthreads();
+
+    long long tiles = 0, rect = 0;
+    for (int w = threadIdx.x; w < n_items_max; w += RANGES_THREADS) {
+        if (w < n_items) {
+            const Item it = make_item(w);
+            const int c = it.b_count;
+            int rank = 0;
+            for (int u = 0; u < n_items; ++u) {
+                const int cu = s_cost[u];
+                rank += (cu > c) || (cu == c && u < w);
+            }
+            int32_t* o = work_out + (size_t)rank * WORK_STRIDE;
+            o[0] = it.a_begin; o[1] = it.a_count; o[2] = it.b_begin; o[3] = it.b_count;
+            o[4] = it.b_extra; o[5] = it.bucket; o[6] = 0; o[7] = 0;
+            tiles += (it.b_count + tile_b - 1) / tile_b;
+            rect += (long long)it.a_count * it.b_count;
+        } else {
+            int32_t* o = work_out + (size_t)w * WORK_STRIDE;
+#pragma unroll
+            for (int i = 0; i < WORK_STRIDE; ++i) o[i] = 0;
+        }
+    }
+    // block reduction of the two counters
+    __shared__ long long s_red[2][RANGES_THREADS / 64];
+    for (int off = 32; off > 0; off >>= 1) {
+        tiles += __shfl_down(tiles, off);
+        rect += __shfl_down(rect, off);
+    }
+    if ((threadIdx.x & 63) == 0) { s_red[0][threadIdx.x >> 6] = tiles; s_red[1][threadIdx.x >> 6] = rect; }
+    __syncthreads();
+    if (threadIdx.x == 0 && counters2) {
+        long long t = 0, r = 0;
+        for (int i = 0; i < RANGES_THREADS / 64; ++i) { t += s_red[0][i]; r += s_red[1][i]; }
+        counters2[0] = t; counters2[1] = r;
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
+    int variant, const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const int32_t* __restrict__ q_off_g, const int32_t* __restrict__ k_off_g, int T, int nb,
+    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
+    int32_t* __restrict__ fwd_work, int32_t* __restrict__ bwd_work, long long* __restrict__ counters)
+{
+    extern __shared__ int32_t smem[];
+    int32_t* s_qoff = smem;                   // [nb+1]
+    int32_t* s_koff = s_qoff + nb + 1;        // [nb+1]
+    int32_t* s_tile_base = s_koff + nb + 1;   // [nb+1]
+    int32_t* s_cost = s_tile_base + nb + 1;   // [max(n_fwd, n_bwd)]
+    const int s = blockIdx.x;
+    if (variant == SCFA_QKDROP) {
+        if (threadIdx.x == 0) {
+            s_qoff[0] = 0; s_qoff[1] = min(max(q_off_g[s], 0), T);
+            s_koff[0] = 0; s_koff[1] = min(max(k_off_g[s], 0), T);
+        }
+    } else {
+        for (int b = threadIdx.x; b <= nb; b += RANGES_THREADS) {
+            s_qoff[b] = q_off_g[(size_t)s * (nb + 1) + b];
+            s_koff[b] = k_off_g[(size_t)s * (nb + 1) + b];
+        }
+    }
+    __syncthreads();
+    const int32_t* qi = q_idx + (size_t)s * T;
+    const int32_t* ki = k_idx + (size_t)s * T;
+    long long* cnt = counters ? counters + (size_t)s * 4 : nullptr;
+    build_list<true>(qi, ki, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd,
+                     fwd_work + (size_t)s * n_fwd * WORK_STRIDE, cnt, s_tile_base, s_cost);
+    if (bwd_work)
+        build_list<false>(ki, qi, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd,
+                          bwd_work + (size_t)s * n_bwd * WORK_STRIDE, cnt ? cnt + 2 : nullptr,
+                          s_tile_base, s_cost);
+    else if (cnt && threadIdx.x == 0) { cnt[2] = 0; cnt[3] = 0; }
+}
+
+int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
+                        const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
+                        int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
+                        int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st)
+{
+    const int n_max = n_fwd > n_bwd ? n_fwd : n_bwd;
+    const size_t smem = sizeof(int32_t) * (3 * (size_t)(nb + 1) + (size_t)n_max);
+    ProfScope prof(SCFA_K_RANGES, st);
+    hipLaunchKernelGGL(block_ranges_kernel, dim3(S), dim3(RANGES_THREADS), smem, st, variant, q_idx,
+                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, fwd_work,
+                       bwd_work, (long long*)counters);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+}  // namespace scfa

@@ -1,0 +1,58 @@
+"""The C-ABI library loads and exports every symbol declared in include/scfa.h.
+No compute calls: this runs without a GPU."""
+import ctypes
+import os
+import re
+
+from paper_2306_01160_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "scfa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(scfa_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert len(names) >= 15
+    L = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), f"{n} is declared in scfa.h but not exported"
+    assert sorted(binding.EXPORTS) == names, "binding.EXPORTS and scfa.h disagree"
+
+
+def test_host_only_entry_points():
+    assert binding.scfa_version() >= 100
+    assert binding.scfa_num_work_items(8192, 16, 128) == 64 + 16
+    assert binding.scfa_num_work_items(100, 1, 128) == 2
+    assert binding.scfa_tile_config(64, binding.SCFA_BF16) == (128, 64, 128, 64)
+    L = binding.lib()
+    assert L.scfa_error_string(binding.SCFA_EWORKSPACE) == b"workspace too small"
+    assert binding.scfa_attn_bwd_workspace_bytes(2, 100, 64, binding.SCFA_BF16) >= 2 * 100 * 64 * 2 + 2 * 2 * 100 * 4
+    assert binding.scfa_attn_bwd_workspace_bytes(2, 100, 64, binding.SCFA_F32) == 0
+
+
+def test_argument_checks_reject_before_any_launch():
+    """Null pointers / bad sizes return error codes from the host-side checks."""
+    L = binding.lib()
+    assert L.scfa_sort_by_bucket(None, 1, 8, 2, None, None, None, None) == binding.SCFA_EINVAL
+    assert L.scfa_compact_keep(None, 1, 8, None, None, None) == binding.SCFA_EINVAL
+    assert L.scfa_gather_rows(None, None, None, 1, 8, 64, 0, None, None) == binding.SCFA_EINVAL
+    one = ctypes.c_void_p(16)   # never dereferenced: checks fail first
+    assert L.scfa_sort_by_bucket(one, 1, 8, 100000, one, one, one, None) == binding.SCFA_EUNSUPPORTED
+    assert L.scfa_sort_by_bucket(one, 0, 8, 2, one, one, one, None) == binding.SCFA_EINVAL
+    assert L.scfa_gather_rows(one, one, None, 1, 8, 3, 0, one, None) == binding.SCFA_EINVAL      # 6-byte rows
+    assert L.scfa_gather_rows(one, one, None, 1, 8, 64, 7, one, None) == binding.SCFA_EUNSUPPORTED
+    assert L.scfa_block_ranges(1, one, one, one, one, 1, 8, 2, 128, 64, 128, 64, 0, one, one, None, None) == binding.SCFA_EINVAL
+    assert L.scfa_block_ranges(0, one, one, one, one, 1, 8, 2, 100, 64, 128, 64, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED
+    assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 48, 0, 0.125, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED
+    assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, -1.0, 0, one, one, None, None) == binding.SCFA_EINVAL
+    assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, 0.125, 1, one, one, None, None) == binding.SCFA_EUNSUPPORTED
+    ws = ctypes.c_void_p(256)
+    assert L.scfa_hash_attn_bwd(one, one, one, one, one, one, 1, one, 1, one, None, one, one, 1, 1, 8, 64, 0, 0.125, 0,
+                                one, one, one, ws, 16, None) == binding.SCFA_EWORKSPACE
+    assert L.scfa_hash_attn_bwd(one, one, one, one, one, one, 1, one, 1, one, None, one, one, 1, 1, 8, 64, 1, 0.125, 0,
+                                one, one, one, ws, 1 << 20, None) == binding.SCFA_EUNSUPPORTED

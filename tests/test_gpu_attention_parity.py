@@ -1,0 +1,168 @@
+"""GPU attention (forward and backward, both variants) vs the fp64 oracle, element by
+element in ORIGINAL order, at sizes that span several tiles and ragged tails, on the
+degenerate cases, and at the five benchmark configurations.
+
+Tolerances (bf16 inputs, fp32 accumulation): max-abs 2e-2 on O, dQ, dK, dV and 1e-3 on
+the logsumexp; fp32 path: 1e-4 on O and 1e-5 on the logsumexp.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2306_01160_amd import workloads as W
+
+from gpu_util import assert_within, compare_backward, compare_forward, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _full_check(wl, backward=True):
+    o, lse, grads, ctx = run_gpu(wl, backward=backward)
+    errs = compare_forward(wl, o, lse)
+    if backward:
+        errs.update(compare_backward(wl, grads))
+    print(wl.name, {k: f"{v:.2e}" for k, v in errs.items()})
+    assert_within(errs, wl.dtype)
+    return errs
+
+
+# --------------------------------------------------------------- small / ragged
+
+def test_config1_hash_fp32_forward():
+    _full_check(W.config1(), backward=False)
+
+
+@pytest.mark.parametrize("T,nb,d", [(256, 4, 64), (333, 3, 64), (1000, 2, 128), (130, 1, 64), (64, 8, 128),
+                                    (1, 1, 64), (700, 16, 64)])
+def test_hash_fp32_forward_shapes(T, nb, d):
+    _full_check(W.hash_uniform(100 + T, 1, 2, T, d, nb, dtype="f32", passes="fwd"), backward=False)
+
+
+@pytest.mark.parametrize("T,nb,d", [(256, 4, 64), (333, 3, 64), (1000, 2, 128), (130, 1, 64), (2049, 1, 64),
+                                    (64, 8, 128), (1, 1, 64), (700, 16, 64), (1500, 4, 128)])
+def test_hash_bf16_forward_backward_shapes(T, nb, d):
+    _full_check(W.hash_uniform(200 + T, 2, 2, T, d, nb))
+
+
+@pytest.mark.parametrize("T,pq,pk,d", [(512, 0.5, 0.5, 64), (777, 0.3, 0.7, 64), (1025, 1.0, 1.0, 64),
+                                       (900, 0.7, 0.2, 128), (65, 0.5, 0.5, 128)])
+def test_qkdrop_bf16_forward_backward_shapes(T, pq, pk, d):
+    _full_check(W.qkdrop_bernoulli(300 + T, 1, 3, T, d, pq, pk))
+
+
+def test_qkdrop_fp32_forward():
+    _full_check(W.qkdrop_bernoulli(7, 1, 2, 300, 64, 0.5, 0.5, dtype="f32", passes="fwd"), backward=False)
+
+
+# --------------------------------------------------------------- degenerate cases
+
+def test_bucket_present_in_q_but_absent_in_k_gives_zero_rows():
+    wl = W.hash_uniform(41, 1, 2, 400, 64, 4)
+    wl.lab_k[wl.lab_k == 2] = 3          # no key in bucket 2: those queries are stranded
+    wl.lab_q[wl.lab_q == 1] = 0          # no query in bucket 1: those keys get zero gradients
+    o, lse, grads, _ = run_gpu(wl)
+    stranded = wl.lab_q == 2
+    assert stranded.any()
+    assert not o.float().cpu().numpy()[stranded].any()
+    assert np.isneginf(lse.cpu().numpy()[stranded]).all()
+    assert not grads[0].cpu().numpy()[stranded].any()
+    orphan_keys = wl.lab_k == 1
+    assert not grads[1].cpu().numpy()[orphan_keys].any() and not grads[2].cpu().numpy()[orphan_keys].any()
+    errs = compare_forward(wl, o, lse); errs.update(compare_backward(wl, grads))
+    assert_within(errs, wl.dtype)
+
+
+def test_zero_kept_keys_and_zero_kept_queries():
+    wl = W.qkdrop_bernoulli(42, 1, 2, 300, 64, 0.5, 0.5)
+    wl.lab_k[0, 0, :] = 0                # head 0: every key dropped
+    wl.lab_q[0, 1, :] = 0                # head 1: every query dropped
+    o, lse, grads, _ = run_gpu(wl)
+    assert not o.float().cpu().numpy().any()
+    assert np.isneginf(lse.cpu().numpy()).all()
+    for g in grads:
+        assert not g.cpu().numpy().any()
+    errs = compare_forward(wl, o, lse); errs.update(compare_backward(wl, grads))
+    assert_within(errs, wl.dtype)
+
+
+def test_first_kept_query_before_first_kept_key():
+    wl = W.qkdrop_bernoulli(43, 1, 1, 200, 64, 1.0, 1.0)
+    wl.lab_k[0, 0, :50] = 0              # queries 0..49 are kept but have no key
+    o, lse, grads, _ = run_gpu(wl)
+    assert not o.float().cpu().numpy()[0, 0, :50].any()
+    errs = compare_forward(wl, o, lse); errs.update(compare_backward(wl, grads))
+    assert_within(errs, wl.dtype)
+
+
+def test_outputs_do_not_depend_on_previous_buffer_contents():
+    """Outputs are fully written: poison-filled output buffers give the same result."""
+    from paper_2306_01160_amd import binding as sc
+    from gpu_util import to_gpu
+    from paper_2306_01160_amd import pipeline
+    wl = W.qkdrop_bernoulli(44, 1, 2, 500, 64, 0.5, 0.5)
+    q, k, v, do, lq, lk = to_gpu(wl)
+    o1, lse1, ctx = pipeline.qkdrop_forward(q, k, v, lq, lk, wl.tau)
+    g1 = pipeline.qkdrop_backward(ctx, do)
+    o2 = torch.full_like(o1, float("nan")); lse2 = torch.full_like(lse1, float("nan"))
+    sc.scfa_qkdrop_attn_fwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_idx, ctx.k_idx, ctx.n_q, ctx.fwd_work, 1, 2, wl.tau,
+                            o_out=o2, lse_out=lse2)
+    outs = tuple(torch.full_like(g, float("nan")) for g in g1)
+    g2 = pipeline.qkdrop_backward(ctx, do, outs=outs)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2) and torch.equal(lse1, lse2)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
+
+
+def test_two_runs_are_bit_identical():
+    """No float atomics anywhere: the path is deterministic."""
+    wl = W.hash_lsh(45, 1, 2, 2048, 64, 8)
+    o1, l1, g1, _ = run_gpu(wl)
+    o2, l2, g2, _ = run_gpu(wl)
+    assert torch.equal(o1, o2) and torch.equal(l1, l2)
+    for a, b in zip(g1, g2):
+        assert torch.equal(a, b)
+
+
+# --------------------------------------------------------------- benchmark configurations
+
+def test_config2_qkdrop_bf16():
+    _full_check(W.config2())
+
+
+def test_config3_hash_lsh_T8192():
+    _full_check(W.config3())
+
+
+def test_config4_hash_lsh_T16384():
+    _full_check(W.config4())
+
+
+def test_config4_dense_twin_sampled():
+    """nb = 1 (dense causal) at T = 16384: the oracle checks sampled rows of two heads."""
+    wl = W.config4(nb=1)
+    o, lse, grads, _ = run_gpu(wl)
+    rows = np.unique(np.concatenate([np.arange(0, 130), np.arange(8000, 8130), np.arange(16384 - 130, 16384),
+                                     np.random.default_rng(0).integers(0, 16384, 64)])).astype(np.int32)
+    segs = [0, 17]
+    errs = compare_forward(wl, o, lse, segs=segs, rows=rows)
+    errs.update(compare_backward(wl, grads, segs=segs, q_rows=rows, k_rows=rows))
+    print(wl.name, errs)
+    assert_within(errs, wl.dtype)
+
+
+def test_config5_qkdrop_T32768_d128_sampled():
+    """B=1, H=16, T=32768, d=128, keep 0.5 (queries) / 0.3 (keys): sampled rows of three heads."""
+    wl = W.config5()
+    o, lse, grads, _ = run_gpu(wl)
+    rows = np.unique(np.concatenate([np.arange(0, 200), np.arange(20000, 20100), np.arange(32768 - 200, 32768),
+                                     np.random.default_rng(1).integers(0, 32768, 100)])).astype(np.int32)
+    segs = [0, 7, 15]
+    errs = compare_forward(wl, o, lse, segs=segs, rows=rows)
+    errs.update(compare_backward(wl, grads, segs=segs, q_rows=rows, k_rows=rows))
+    print(wl.name, errs)
+    assert_within(errs, wl.dtype)
+    # dropped rows are exactly zero everywhere
+    dq = grads[0].cpu().numpy()
+    assert not dq[wl.lab_q == 0].any()
+    assert not o.float().cpu().numpy()[wl.lab_q == 0].any()

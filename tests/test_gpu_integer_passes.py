@@ -1,0 +1,210 @@
+"""GPU integer passes vs the oracle, bit-exact: stable sort by bucket, compaction,
+row gather, and validity of the tile-skip schedule."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2306_01160_amd import binding as sc
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _t(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+@pytest.mark.parametrize("S,T,nb", [(1, 8, 3), (3, 1, 1), (2, 63, 4), (5, 1000, 16), (4, 8192, 16),
+                                    (2, 16384, 8), (1, 32768, 256), (3, 4097, 7), (2, 2048, 1)])
+def test_sort_by_bucket_bit_exact(S, T, nb):
+    rng = np.random.default_rng(S * 1000003 + T * 31 + nb)
+    b = rng.integers(0, nb, (S, T)).astype(np.int32)
+    if nb > 2:
+        b[b == 1] = 0        # leave a bucket empty
+    idx, bs, off = sc.scfa_sort_by_bucket(_t(b), nb)
+    ridx, rbs, roff = oracle.sort_by_bucket(b, nb)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+    assert np.array_equal(bs.cpu().numpy(), rbs)
+    assert np.array_equal(off.cpu().numpy(), roff)
+
+
+def test_sort_fig1_example(golden_dir):
+    import json, os
+    g = json.load(open(os.path.join(golden_dir, "fig1_worked_example.json")))["hash_sparse"]
+    bq = np.array([g["query_bucket_by_position"]], np.int32)
+    bk = np.array([g["key_bucket_by_position"]], np.int32)
+    qi, qs, _ = sc.scfa_sort_by_bucket(_t(bq), 3)
+    ki, ks, _ = sc.scfa_sort_by_bucket(_t(bk), 3)
+    assert qi.cpu().numpy()[0].tolist() == g["sorted_query_positions"]
+    assert ki.cpu().numpy()[0].tolist() == g["sorted_key_positions"]
+    assert qs.cpu().numpy()[0].tolist() == g["sorted_query_buckets"]
+    assert ks.cpu().numpy()[0].tolist() == g["sorted_key_buckets"]
+
+
+def test_sort_clamps_out_of_range_ids():
+    b = np.array([[5, -3, 1, 0, 7, 1]], np.int32)
+    idx, bs, off = sc.scfa_sort_by_bucket(_t(b), 2)
+    ridx, rbs, roff = oracle.sort_by_bucket(np.clip(b, 0, 1), 2)
+    assert np.array_equal(idx.cpu().numpy(), ridx) and np.array_equal(bs.cpu().numpy(), rbs)
+    assert np.array_equal(off.cpu().numpy(), roff)
+
+
+@pytest.mark.parametrize("S,T,p", [(1, 8, 0.5), (2, 1, 1.0), (3, 100, 0.0), (4, 2048, 0.5), (16, 32768, 0.3),
+                                   (2, 5000, 1.0), (3, 777, 0.1)])
+def test_compact_keep_bit_exact(S, T, p):
+    rng = np.random.default_rng(S * 7 + T)
+    keep = (rng.random((S, T)) < p).astype(np.uint8)
+    keep[keep != 0] = rng.integers(1, 255, int(keep.sum())).astype(np.uint8)   # any non-zero value = kept
+    idx, cnt = sc.scfa_compact_keep(_t(keep))
+    ridx, rcnt = oracle.compact_keep(keep)
+    assert np.array_equal(cnt.cpu().numpy(), rcnt)
+    assert np.array_equal(idx.cpu().numpy(), ridx)
+
+
+def test_compact_fig1_example(golden_dir):
+    import json, os
+    g = json.load(open(os.path.join(golden_dir, "fig1_worked_example.json")))["qk_sparse"]
+    kq = np.ones((1, 8), np.uint8); kq[0, g["dropped_queries"]] = 0
+    kk = np.ones((1, 8), np.uint8); kk[0, g["dropped_keys"]] = 0
+    qi, nq = sc.scfa_compact_keep(_t(kq)); ki, nk = sc.scfa_compact_keep(_t(kk))
+    assert qi.cpu().numpy()[0, :int(nq[0])].tolist() == g["kept_queries"]
+    assert ki.cpu().numpy()[0, :int(nk[0])].tolist() == g["kept_keys"]
+
+
+@pytest.mark.parametrize("dtype,d", [(torch.bfloat16, 64), (torch.bfloat16, 128), (torch.float32, 64)])
+def test_gather_rows_bit_exact(dtype, d):
+    S, T = 3, 1237
+    rng = np.random.default_rng(d)
+    x = torch.from_numpy(rng.standard_normal((S, T, d)).astype(np.float32)).to(DEV).to(dtype)
+    idx = np.stack([rng.permutation(T) for _ in range(S)]).astype(np.int32)
+    out = sc.scfa_gather_rows(x, _t(idx))
+    ref = torch.gather(x, 1, _t(idx).long()[..., None].expand(-1, -1, d))
+    assert torch.equal(out, ref)
+    # with counts: rows beyond count[s] are untouched
+    cnt = np.array([0, 500, T], np.int32)
+    sentinel = torch.full_like(x, 7.0)
+    out2 = sc.scfa_gather_rows(x, _t(idx), _t(cnt), out=sentinel.clone())
+    for s in range(S):
+        assert torch.equal(out2[s, :cnt[s]], ref[s, :cnt[s]])
+        assert torch.equal(out2[s, cnt[s]:], sentinel[s, cnt[s]:])
+
+
+# ------------------------------------------------------------------ schedule
+
+def _check_schedule(variant, lab_q, lab_k, nb, tiles):
+    """Several schedules are correct; check what must hold: every allowed pair is covered
+    exactly once, claimed mask-free regions are mask-free, ranges are tight, items are
+    ordered by decreasing work, counters match the emitted items."""
+    fm, fn, bn, bm = tiles
+    S, T = lab_q.shape
+    if variant == sc.SCFA_HASH:
+        q_idx, _, q_off = sc.scfa_sort_by_bucket(_t(lab_q), nb)
+        k_idx, _, k_off = sc.scfa_sort_by_bucket(_t(lab_k), nb)
+        rq, _, _ = oracle.sort_by_bucket(lab_q, nb); rk, _, _ = oracle.sort_by_bucket(lab_k, nb)
+        nq = np.full(S, T); nk = np.full(S, T)
+        ovar = oracle.HASH
+    else:
+        q_idx, q_off = sc.scfa_compact_keep(_t(lab_q))
+        k_idx, k_off = sc.scfa_compact_keep(_t(lab_k))
+        rq, nq = oracle.compact_keep(lab_q); rk, nk = oracle.compact_keep(lab_k)
+        ovar = oracle.QKDROP
+    assert np.array_equal(q_idx.cpu().numpy(), rq) and np.array_equal(k_idx.cpu().numpy(), rk)
+    fwd, bwd, cnt = sc.scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles)
+    torch.cuda.synchronize()
+    fwd, bwd, cnt = fwd.cpu().numpy(), bwd.cpu().numpy(), cnt.cpu().numpy()
+    for s in range(S):
+        M = oracle.allowed_mask(lab_q[s], lab_k[s], ovar)[np.ix_(rq[s], rk[s])]   # permuted coordinates
+        M[nq[s]:, :] = False; M[:, nk[s]:] = False
+        # forward list
+        covered = np.zeros(T, bool)
+        items = fwd[s]
+        live = items[items[:, 1] > 0]
+        assert np.all(items[len(live):] == 0), "unused items must trail and be zero"
+        assert np.all(np.diff(live[:, 3]) <= 0), "forward items must be ordered by decreasing k_count"
+        tiles_f = 0; rect_f = 0
+        for qb, qc, kb, kc, kn, bucket, _, _ in live:
+            assert 0 < qc <= fm and 0 <= kn <= kc
+            assert not covered[qb:qb + qc].any(); covered[qb:qb + qc] = True
+            sub = M[qb:qb + qc]
+            assert not sub[:, :kb].any() and not sub[:, kb + kc:].any(), "allowed pair outside the key range"
+            assert sub[:, kb:kb + kn].all(), "mask-free prefix contains a masked pair"
+            if kc:
+                assert sub[:, kb + kc - 1].any(), "key range is not tight"
+            if kn < kc:
+                assert not sub[:, kb + kn].all(), "mask-free prefix is not maximal"
+            tiles_f += -(-kc // fn); rect_f += qc * kc
+        assert np.array_equal(covered[:nq[s]], np.ones(nq[s], bool)) and not covered[nq[s]:].any()
+        # backward list
+        covered = np.zeros(T, bool)
+        items = bwd[s]
+        live = items[items[:, 1] > 0]
+        assert np.all(items[len(live):] == 0)
+        assert np.all(np.diff(live[:, 3]) <= 0)
+        tiles_b = 0; rect_b = 0
+        for kb, kc, qb, qc, qm, bucket, _, _ in live:
+            assert 0 < kc <= bn and 0 <= qm <= qc
+            assert not covered[kb:kb + kc].any(); covered[kb:kb + kc] = True
+            sub = M[:, kb:kb + kc]
+            assert not sub[:qb].any() and not sub[qb + qc:].any(), "allowed pair outside the query range"
+            assert sub[qb + qm:qb + qc].all(), "unmasked query rows contain a masked pair"
+            if qc:
+                assert sub[qb].any(), "query range is not tight"
+            if qm:
+                assert not sub[qb + qm - 1].all()
+            tiles_b += -(-qc // bm); rect_b += qc * kc
+        assert np.array_equal(covered[:nk[s]], np.ones(nk[s], bool)) and not covered[nk[s]:].any()
+        assert cnt[s].tolist() == [tiles_f, rect_f, tiles_b, rect_b]
+
+
+@pytest.mark.parametrize("S,T,nb", [(2, 700, 4), (1, 2048, 16), (3, 300, 1), (1, 129, 3), (2, 64, 8)])
+def test_schedule_hash(S, T, nb):
+    rng = np.random.default_rng(T + nb)
+    bq = rng.integers(0, nb, (S, T)).astype(np.int32)
+    bk = rng.integers(0, nb, (S, T)).astype(np.int32)
+    if nb > 2:
+        bk[bk == 2] = 0          # a bucket present in Q but absent in K
+        bq[bq == 1] = 0          # and one present in K but absent in Q
+    _check_schedule(sc.SCFA_HASH, bq, bk, nb, sc.scfa_tile_config(64, sc.SCFA_BF16))
+
+
+@pytest.mark.parametrize("S,T,pq,pk", [(2, 900, 0.5, 0.5), (1, 2048, 0.3, 0.7), (2, 257, 1.0, 1.0),
+                                       (2, 300, 0.0, 0.5), (2, 300, 0.5, 0.0)])
+def test_schedule_qkdrop(S, T, pq, pk):
+    rng = np.random.default_rng(T)
+    kq = (rng.random((S, T)) < pq).astype(np.uint8)
+    kk = (rng.random((S, T)) < pk).astype(np.uint8)
+    _check_schedule(sc.SCFA_QKDROP, kq, kk, 1, sc.scfa_tile_config(64, sc.SCFA_BF16))
+
+
+def test_schedule_regular_case_is_lower_triangular():
+    """No sparsity: the computed tile set coincides with FlashAttention's (Fig. 2, left),
+    and never exceeds what the paper's Alg. 2 range rule computes."""
+    T = 1024
+    fm, fn, bn, bm = tiles = sc.scfa_tile_config(64, sc.SCFA_BF16)
+    lab = np.zeros((1, T), np.int32)
+    q_idx, _, q_off = sc.scfa_sort_by_bucket(_t(lab), 1)
+    fwd, bwd, cnt = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, q_idx, q_off, q_off, 1, tiles)
+    fwd = fwd.cpu().numpy()[0]
+    live = fwd[fwd[:, 1] > 0]
+    got = sorted((int(qb) // fm, -(-int(kc) // fn)) for qb, qc, kb, kc, kn, *_ in live)
+    assert got == [(i, (i + 1) * fm // fn) for i in range(T // fm)]
+    ref = oracle.paper_tile_ranges_hash(np.arange(T), np.arange(T), lab[0], lab[0], fm, fn)
+    assert int(cnt[0, 0]) == sum(e - a for a, e in ref)
+
+
+def test_schedule_computes_no_more_than_paper_rule():
+    """On LSH-like bucket sizes the bucket-anchored tiles cover no more area than the
+    ranges of Alg. 2 with the same tile shape (the paper notes its tiles straddle bucket
+    boundaries, App. C)."""
+    S, T, nb = 2, 4096, 16
+    fm, fn, bn, bm = tiles = sc.scfa_tile_config(64, sc.SCFA_BF16)
+    rng = np.random.default_rng(5)
+    bq = rng.integers(0, nb, (S, T)).astype(np.int32); bk = rng.integers(0, nb, (S, T)).astype(np.int32)
+    q_idx, q_bs, q_off = sc.scfa_sort_by_bucket(_t(bq), nb)
+    k_idx, k_bs, k_off = sc.scfa_sort_by_bucket(_t(bk), nb)
+    _, _, cnt = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles)
+    for s in range(S):
+        ref = oracle.paper_tile_ranges_hash(q_idx[s].cpu().numpy(), k_idx[s].cpu().numpy(),
+                                            q_bs[s].cpu().numpy(), k_bs[s].cpu().numpy(), fm, fn)
+        assert int(cnt[s, 0]) <= sum(e - a for a, e in ref)
