@@ -47,6 +47,7 @@ extern "C" {
 
 #define SCFA_BF16 0             /* 16-bit brain float, fp32 accumulation */
 #define SCFA_F32  1             /* fp32 (forward only) */
+#define SCFA_F16  2             /* compute format of the permuted copies of bf16 tensors */
 
 #define SCFA_HASH   0
 #define SCFA_QKDROP 1
@@ -101,9 +102,13 @@ int scfa_compact_keep(const uint8_t *keep, int S, int T,
  * compacted Q, K, V the kernels consume).  x and out must be 16-byte aligned
  * and must not overlap.  dtype: SCFA_BF16 or SCFA_F32; d*sizeof(elem) must be a
  * multiple of 16.
+ * out_dtype: equal to dtype (bit-exact copy), or SCFA_F16 for SCFA_BF16 input: the
+ * compute format of the attention kernels.  bf16 -> fp16 rounds to nearest even; it is
+ * exact for magnitudes in [2^-17, 65504], smaller ones lose low bits (absolute error
+ * < 2^-25), larger ones saturate at 65504.
  */
 int scfa_gather_rows(const void *x, const int32_t *idx, const int32_t *count,
-                     int S, int T, int d, int dtype, void *out, void *stream);
+                     int S, int T, int d, int dtype, int out_dtype, void *out, void *stream);
 
 /* ------------------------------------------------------------------------
  * a4. Tile-skip schedule.  The paper finds, per block of queries, the range of
@@ -161,7 +166,9 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  * per-tile work of Alg. 1 / Alg. 2: scores, causal mask on original positions,
  * online softmax with the NaN-safe handling of fully masked rows, P.V).
  *
- *   q_perm,k_perm,v_perm  [S,T,d] rows in sorted (hash) or compacted (qkdrop) order
+ *   q_perm,k_perm,v_perm  [S,T,d] rows in sorted (hash) or compacted (qkdrop) order, as
+ *                         scfa_gather_rows writes them: fp32 for SCFA_F32, fp16
+ *                         (out_dtype = SCFA_F16) for SCFA_BF16
  *   q_idx,k_idx           [S,T] original positions of those rows
  *   fwd_work, n_fwd       work list of scfa_block_ranges
  *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d))

@@ -14,11 +14,11 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libscfa.so")
+LIB_PATH = os.environ.get("SCFA_LIB", os.path.join(_HERE, "libscfa.so"))
 
 SCFA_OK = 0
 SCFA_EINVAL, SCFA_EUNSUPPORTED, SCFA_EWORKSPACE, SCFA_EHIP = -1, -2, -3, -4
-SCFA_BF16, SCFA_F32 = 0, 1
+SCFA_BF16, SCFA_F32, SCFA_F16 = 0, 1, 2
 SCFA_HASH, SCFA_QKDROP = 0, 1
 SCFA_WORK_STRIDE = 8
 KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_prep": 5,
@@ -53,7 +53,7 @@ def lib():
         L.scfa_error_string.argtypes = [ci]
         L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp]
-        L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, vp, vp]
+        L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, vp]
         L.scfa_block_ranges.argtypes = [ci, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_num_work_items.argtypes = [ci, ci, ci]
         ip = ctypes.POINTER(ci)
@@ -96,11 +96,16 @@ def _stream():
 
 
 def dtype_code(t: torch.Tensor) -> int:
-    if t.dtype == torch.bfloat16:
+    if t.dtype in (torch.bfloat16, torch.float16):   # fp16 = compute format of bf16 tensors
         return SCFA_BF16
     if t.dtype == torch.float32:
         return SCFA_F32
     raise ScfaError(f"unsupported dtype {t.dtype}")
+
+
+def _out_dtype(x_perm: torch.Tensor):
+    """O has the dtype of the original tensors: bf16 when the permuted copies are fp16."""
+    return torch.bfloat16 if x_perm.dtype == torch.float16 else x_perm.dtype
 
 
 # ---------------------------------------------------------------- entry points
@@ -140,13 +145,15 @@ def scfa_compact_keep(keep: torch.Tensor):
     return idx, count
 
 
-def scfa_gather_rows(x: torch.Tensor, idx: torch.Tensor, count=None, out=None):
-    """x [S,T,d], idx [S,T] -> out [S,T,d] with out[s,r] = x[s, idx[s,r]] for r < count[s] (or T)."""
+def scfa_gather_rows(x: torch.Tensor, idx: torch.Tensor, count=None, out=None, to_f16=False):
+    """x [S,T,d], idx [S,T] -> out [S,T,d] with out[s,r] = x[s, idx[s,r]] for r < count[s] (or T).
+    to_f16: bf16 input is written in the fp16 compute format of the attention kernels."""
     S, T, d = x.shape
     if out is None:
-        out = torch.empty_like(x)
-    _check(lib().scfa_gather_rows(_ptr(x), _ptr(idx), _ptr(count), S, T, d, dtype_code(x), _ptr(out), _stream()),
-           "scfa_gather_rows")
+        out = torch.empty(x.shape, dtype=torch.float16 if to_f16 else x.dtype, device=x.device)
+    out_code = SCFA_F16 if to_f16 else dtype_code(x)
+    _check(lib().scfa_gather_rows(_ptr(x), _ptr(idx), _ptr(count), S, T, d, dtype_code(x), out_code, _ptr(out),
+                                  _stream()), "scfa_gather_rows")
     return out
 
 
@@ -170,7 +177,7 @@ def scfa_hash_attn_fwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, B, H, sm_
                        o_f32_out=None):
     S, T, d = q_perm.shape
     assert S == B * H
-    o = torch.empty((B, H, T, d), dtype=q_perm.dtype, device=q_perm.device) if o_out is None else o_out
+    o = torch.empty((B, H, T, d), dtype=_out_dtype(q_perm), device=q_perm.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_perm.device) if lse_out is None else lse_out
     _check(lib().scfa_hash_attn_fwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
                                     _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_perm),
@@ -183,7 +190,7 @@ def scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_sc
                          o_f32_out=None):
     S, T, d = q_c.shape
     assert S == B * H
-    o = torch.empty((B, H, T, d), dtype=q_c.dtype, device=q_c.device) if o_out is None else o_out
+    o = torch.empty((B, H, T, d), dtype=_out_dtype(q_c), device=q_c.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_c.device) if lse_out is None else lse_out
     _check(lib().scfa_qkdrop_attn_fwd(_ptr(q_c), _ptr(k_c), _ptr(v_c), _ptr(q_idx), _ptr(k_idx), _ptr(n_q),
                                       _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_c),

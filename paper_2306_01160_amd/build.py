@@ -18,13 +18,19 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscfa.so")
 
-SOURCES = ["scfa_api.hip", "scfa_index.hip", "scfa_ranges.hip", "scfa_attn_f32.hip", "scfa_attn_bf16.hip"]
+SOURCES = ["scfa_api.hip", "scfa_index.hip", "scfa_ranges.hip", "scfa_attn_f32.hip", "scfa_attn_fwd.hip",
+           "scfa_attn_bf16.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # packed fp32 VALU forms are kept off on this machine pool
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # keep MFMA accumulators in VGPRs (no accumulation-register copies around the softmax)
+    "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+    # no kernel forms a NaN on purpose (masked scores are -inf, never inf - inf); this lets
+    # max/min skip the quieting of signalling NaNs
+    "-fno-honor-nans",
     "-Wall", "-Wno-unused-function",
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
@@ -43,19 +49,20 @@ def _compile(src: str, extra) -> str:
     return obj
 
 
-def build(verbose: bool = False, extra_flags=()) -> str:
+def build(verbose: bool = False, extra_flags=(), lib: str = LIB) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         objs = list(ex.map(lambda s: _compile(s, list(extra_flags)), SOURCES))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("link failed:\n" + res.stderr)
     if verbose:
-        print(LIB)
-    return LIB
+        print(lib)
+    return lib
 
 
 if __name__ == "__main__":
     extra = [a for a in sys.argv[1:] if a.startswith("-")]
-    build(verbose=True, extra_flags=extra)
+    out = [a for a in sys.argv[1:] if not a.startswith("-")]
+    build(verbose=True, extra_flags=extra, lib=out[0] if out else LIB)

@@ -170,14 +170,15 @@ int scfa_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32
 }
 
 int scfa_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T, int d, int dtype,
-                     void* out, void* stream)
+                     int out_dtype, void* out, void* stream)
 {
     if (!x || !idx || !out || S <= 0 || T <= 0 || d <= 0) return SCFA_EINVAL;
     if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
+    if (out_dtype != dtype && !(dtype == SCFA_BF16 && out_dtype == SCFA_F16)) return SCFA_EUNSUPPORTED;
     const long long row_bytes = (long long)d * (dtype == SCFA_BF16 ? 2 : 4);
     if (row_bytes % 16 != 0 || !aligned16(x) || !aligned16(out)) return SCFA_EINVAL;
     if (S > 65535 || (long long)T * (row_bytes / 16) / 256 > 0x7fffffffLL) return SCFA_EUNSUPPORTED;
-    return launch_gather_rows(x, idx, count, S, T, (int)row_bytes, out, (hipStream_t)stream);
+    return launch_gather_rows(x, idx, count, S, T, (int)row_bytes, out_dtype != dtype, out, (hipStream_t)stream);
 }
 
 int scfa_num_work_items(int T, int nb, int tile)

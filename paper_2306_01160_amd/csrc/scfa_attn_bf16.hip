@@ -145,190 +145,6 @@ __device__ __forceinline__ f16x8 lds_a_trans(const uint32_t* lds, int dd, int ch
 }
 
 // ===========================================================================
-// Forward
-// ===========================================================================
-template <int D>
-__global__ __launch_bounds__(256) void attn_fwd_bf16_kernel(
-    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
-    const int32_t* __restrict__ work, int n_work, int S, int T, float tau,
-    uint16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ o_f32)
-{
-    constexpr int BN = FWD_TILE_N;
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[BN * (D + 8)];
-    __shared__ __attribute__((aligned(16))) uint32_t Vt[D * (BN / 2 + 1)];
-    __shared__ __attribute__((aligned(16))) int32_t kpos_s[BN];
-
-    // consecutive workgroups take the same work rank of consecutive segments: the
-    // longest items of every segment are dispatched first, and when S is a multiple
-    // of 8 a segment stays on one XCD (its K/V stay in that XCD's L2).
-    const int s = blockIdx.x % S;
-    const int w = blockIdx.x / S;
-    const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
-    const int q_begin = it[W_QBEGIN], q_count = it[W_QCOUNT];
-    const int k_begin = it[W_KBEGIN], k_count = it[W_KCOUNT], k_nomask = it[W_KNOMASK];
-    if (q_count <= 0) return;
-
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
-    const size_t seg = (size_t)s * T;
-    const int qrow = wave * 32 + l32;
-    const bool qvalid = qrow < q_count;
-    const int qpos = qvalid ? q_idx[seg + q_begin + qrow] : -1;
-
-    bf16x8 qf[D / 16];
-    {
-        const uint16_t* qp = q + (seg + q_begin + qrow) * D + h * 8;
-#pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
-            qf[kk] = as_bf16x8(qvalid ? *reinterpret_cast<const uint4*>(qp + kk * 16) : make_uint4(0u, 0u, 0u, 0u));
-    }
-
-    f32x16 oacc[D / 32];
-#pragma unroll
-    for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[db][i] = 0.f;
-    float m = -INFINITY, lsum = 0.f;
-    const float c = tau * LOG2E;
-
-    const uint16_t* kbase = k + (seg + k_begin) * D;
-    const uint16_t* vbase = v + (seg + k_begin) * D;
-    const int32_t* kib = k_idx + seg + k_begin;
-    const int n_tiles = (k_count + BN - 1) / BN;
-
-    PairTile<D, BN> kt, vt;
-    int kp_reg = INT32_MAX;
-    if (n_tiles > 0) {
-        kt.load(kbase, k_count);
-        vt.load(vbase, k_count);
-        if (tid < BN) kp_reg = tid < k_count ? kib[tid] : INT32_MAX;
-        kt.store_rows(Ks);
-        vt.store_trans(Vt);
-        if (tid < BN) kpos_s[tid] = kp_reg;
-    }
-    __syncthreads();
-
-    for (int jt = 0; jt < n_tiles; ++jt) {
-        const bool more = jt + 1 < n_tiles;
-        if (more) {
-            const int r0 = (jt + 1) * BN;
-            kt.load(kbase + (size_t)r0 * D, k_count - r0);
-            vt.load(vbase + (size_t)r0 * D, k_count - r0);
-            if (tid < BN) kp_reg = r0 + tid < k_count ? kib[r0 + tid] : INT32_MAX;
-        }
-
-        // S^T = K Q^T : two blocks of 32 keys x 32 queries
-        f32x16 sacc[2];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sacc[kb][i] = 0.f;
-#pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-                sacc[kb] = mfma32(lds_a_rows<D>(Ks, kb * 32 + l32, kk * 16 + h * 8), qf[kk], sacc[kb]);
-
-        if ((jt + 1) * BN > k_nomask) {   // causal test on original positions
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_s[kb * 32 + 8 * g + 4 * h]);
-                    if (kp.x > qpos) sacc[kb][4 * g + 0] = -INFINITY;
-                    if (kp.y > qpos) sacc[kb][4 * g + 1] = -INFINITY;
-                    if (kp.z > qpos) sacc[kb][4 * g + 2] = -INFINITY;
-                    if (kp.w > qpos) sacc[kb][4 * g + 3] = -INFINITY;
-                }
-        }
-
-        float mx = -INFINITY;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[kb][i]);
-        mx = fmaxf(mx, xhalf(mx));
-        const float m_new = fmaxf(m, mx);
-        const float m_use = m_new == -INFINITY ? 0.f : m_new;
-        const float alpha = fast_exp2((m - m_use) * c);
-        const float mc = m_use * c;
-        float psum = 0.f;
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p = fast_exp2(fmaf(sacc[kb][i], c, -mc));
-                sacc[kb][i] = p;
-                psum += p;
-            }
-        lsum = lsum * alpha + psum;
-        m = m_new;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) oacc[db][i] *= alpha;
-
-        // O^T += V^T P^T
-        f16x8 pf[4];
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) pf[c4] = pack_chunk(sacc[c4 >> 1], c4 & 1);
-#pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4)
-#pragma unroll
-            for (int db = 0; db < D / 32; ++db)
-                oacc[db] = mfma32(lds_a_trans<BN>(Vt, db * 32 + l32, c4, h), pf[c4], oacc[db]);
-
-        __syncthreads();
-        if (more) {
-            kt.store_rows(Ks);
-            vt.store_trans(Vt);
-            if (tid < BN) kpos_s[tid] = kp_reg;
-        }
-        __syncthreads();
-    }
-
-    const float ltot = lsum + xhalf(lsum);
-    const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
-    if (qvalid) {
-        uint16_t* op = o + (seg + qpos) * D + 4 * h;
-#pragma unroll
-        for (int db = 0; db < D / 32; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                __bf16 x0 = (__bf16)(oacc[db][4 * g + 0] * inv), x1 = (__bf16)(oacc[db][4 * g + 1] * inv);
-                __bf16 x2 = (__bf16)(oacc[db][4 * g + 2] * inv), x3 = (__bf16)(oacc[db][4 * g + 3] * inv);
-                uint2 pk;
-                pk.x = (uint32_t)__builtin_bit_cast(uint16_t, x0) | ((uint32_t)__builtin_bit_cast(uint16_t, x1) << 16);
-                pk.y = (uint32_t)__builtin_bit_cast(uint16_t, x2) | ((uint32_t)__builtin_bit_cast(uint16_t, x3) << 16);
-                *reinterpret_cast<uint2*>(op + db * 32 + 8 * g) = pk;
-                if (o_f32)
-                    *reinterpret_cast<float4*>(o_f32 + (seg + qpos) * D + 4 * h + db * 32 + 8 * g) =
-                        make_float4(oacc[db][4 * g + 0] * inv, oacc[db][4 * g + 1] * inv, oacc[db][4 * g + 2] * inv,
-                                    oacc[db][4 * g + 3] * inv);
-            }
-        if (h == 0) lse[seg + qpos] = ltot > 0.f ? fmaf(m, tau, logf(ltot)) : -INFINITY;
-    }
-}
-
-int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
-                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
-                         float tau, void* o, float* lse, float* o_f32, hipStream_t st)
-{
-    dim3 grid((unsigned)((size_t)S * n_work)), block(256);
-    ProfScope prof(SCFA_K_FWD, st);
-    if (d == 64)
-        hipLaunchKernelGGL(attn_fwd_bf16_kernel<64>, grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)k,
-                           (const uint16_t*)v, q_idx, k_idx, work, n_work, S, T, tau, (uint16_t*)o, lse, o_f32);
-    else if (d == 128)
-        hipLaunchKernelGGL(attn_fwd_bf16_kernel<128>, grid, block, 0, st, (const uint16_t*)q, (const uint16_t*)k,
-                           (const uint16_t*)v, q_idx, k_idx, work, n_work, S, T, tau, (uint16_t*)o, lse, o_f32);
-    else
-        return SCFA_EUNSUPPORTED;
-    SCFA_HIP_TRY(hipGetLastError());
-    return SCFA_OK;
-}
-
-// ===========================================================================
 // Backward pre-pass: D_i = <dO_i, O_i>, and dO, D, LSE brought into permuted order.
 // One row is handled by D/8 adjacent lanes (16 bytes each).
 // ===========================================================================

@@ -1,0 +1,297 @@
+// Forward attention over the work list, fp16 compute format, fp32 accumulation.
+//
+// A workgroup owns one work item: 128 query rows of one bucket and the range of keys
+// of the same bucket that causality can let through (scfa_block_ranges).  Keys are
+// walked 64 at a time; tiles the schedule proved mask-free come first and run without
+// any test, the remaining (diagonal) tiles apply the causal test on original positions
+// (paper Sec. 3.1 / 3.2: a local causal mask from the index vectors).
+//
+// A wavefront keeps its query rows in the lanes: S^T = K Q^T puts one query per lane
+// (column) and 16 keys per accumulator block in its registers, so the softmax
+// statistics are per-lane scalars and S^T's accumulator layout is already the
+// B-operand layout of O^T += V^T P^T.  V^T comes from the row-major V tile through
+// transposing LDS reads.
+//
+// Online softmax (paper App. B.1, running maximum and sum, NaN-safe for fully masked
+// rows): the accumulator is un-normalised and divided by the sum once at the end.  The
+// reference maximum m is only raised when some row's tile maximum exceeds it by more
+// than 2^LAZY_LOG2 (then the accumulator and the sum are rescaled by exp(m_old - m_new));
+// between raises P = exp(s - m) may exceed 1 but stays far inside the fp16 range.  A
+// row that never sees an allowed key keeps m = -inf and l = 0; its exponent base is 0
+// (the paper's replacement of -inf by 0), every p is exp(-inf) = 0, and it is written
+// as zeros with LSE = -inf.
+#include "scfa_common.hpp"
+#include "scfa_mma.hpp"
+
+#include <math.h>
+#include <stdlib.h>
+
+#include <type_traits>
+
+namespace scfa {
+
+constexpr float LAZY_LOG2 = 6.0f;
+
+template <int D, int NW, int QB>
+__global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau,
+    uint16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ o_f32)
+{
+    static_assert(NW * QB * 32 == FWD_TILE_M, "workgroup must cover the forward query tile");
+    constexpr int BN = FWD_TILE_N;
+    constexpr int THREADS = NW * 64;
+    constexpr int KST = D + 8;    // K tile row stride: 16-byte row reads conflict-free
+    constexpr int VST = D + 16;   // V tile row stride: transposing reads conflict-free
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    uint16_t (*Ks)[BN * KST] = reinterpret_cast<uint16_t (*)[BN * KST]>(smem_raw);
+    uint16_t (*Vs)[BN * VST] = reinterpret_cast<uint16_t (*)[BN * VST]>(smem_raw + 2 * BN * KST * 2);
+    int32_t (*kpos_s)[BN] = reinterpret_cast<int32_t (*)[BN]>(smem_raw + 2 * BN * (KST + VST) * 2);
+
+    // consecutive workgroups take the same work rank of consecutive segments: the longest
+    // items of every segment are dispatched first, and when S is a multiple of 8 a segment
+    // stays on one XCD (its K/V stay in that XCD's L2).
+    const int s = blockIdx.x % S;
+    const int w = blockIdx.x / S;
+    const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
+    const int q_begin = it[W_QBEGIN], q_count = it[W_QCOUNT];
+    const int k_begin = it[W_KBEGIN], k_count = it[W_KCOUNT], k_nomask = it[W_KNOMASK];
+    if (q_count <= 0) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const size_t seg = (size_t)s * T;
+
+    int qrow[QB], qpos[QB];
+    bool qvalid[QB];
+    f16x8 qf[QB][D / 16];
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+        qrow[b] = (wave * QB + b) * 32 + l32;
+        qvalid[b] = qrow[b] < q_count;
+        const int qr = min(qrow[b], q_count - 1);          // rows past the end repeat the last one
+        const int qp_ = q_idx[seg + q_begin + qr];
+        qpos[b] = qvalid[b] ? qp_ : -1;                    // position -1: every key is masked
+        const uint16_t* qp = q + (seg + q_begin + qr) * D + h * 8;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) qf[b][kk] = as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16));
+    }
+#pragma unroll
+    for (int b = 0; b < QB; ++b)
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) touch(qf[b][kk]);   // loaded before the tile loop starts
+
+    f32x16 oacc[QB][D / 32];
+    float m[QB], mc[QB], lsum[QB];   // reference max (raw score units), m*c with -inf -> 0, partial row sum
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) oacc[b][db] = zero16();
+        m[b] = -INFINITY; mc[b] = -RTZ_BIAS_LOG2; lsum[b] = 0.f;
+    }
+    const float c = tau * LOG2E;
+    const float lazy = LAZY_LOG2 / c;
+
+    const uint16_t* kbase = k + (seg + k_begin) * D;
+    const uint16_t* vbase = v + (seg + k_begin) * D;
+    const int32_t* kib = k_idx + seg + k_begin;
+    const int n_tiles = (k_count + BN - 1) / BN;
+    const int n_free = k_nomask / BN;            // leading tiles that need no mask
+
+    TileRegs<D, BN, THREADS> kt, vt;
+    const rsrc_t k_rsrc = make_rsrc(kbase, (uint32_t)k_count * D * 2);
+    const rsrc_t v_rsrc = make_rsrc(vbase, (uint32_t)k_count * D * 2);
+    const rsrc_t p_rsrc = make_rsrc(kib, (uint32_t)k_count * 4);
+    int kp_reg = 0, kp_row = 0;
+    auto fetch = [&](int jt) {
+        kt.load(k_rsrc, jt * kt.TILE_BYTES);
+        vt.load(v_rsrc, jt * vt.TILE_BYTES);
+        if (tid < BN) {
+            kp_reg = buffer_load4(p_rsrc, tid * 4, jt * BN * 4);
+            kp_row = jt * BN + tid;
+        }
+    };
+    auto stash = [&](int buf) {
+        kt.template store<KST>(Ks[buf]);
+        vt.template store<VST>(Vs[buf]);
+        if (tid < BN) kpos_s[buf][tid] = kp_row < k_count ? kp_reg : INT32_MAX;   // keys past the end are never allowed
+    };
+
+    auto tile = [&](int buf, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const uint16_t* Kt = Ks[buf];
+        const uint16_t* Vt = Vs[buf];
+        // S^T = K Q^T : [key block kb][query block b]
+        f32x16 sacc[2][QB];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int b = 0; b < QB; ++b) sacc[kb][b] = zero16();
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const f16x8 a = lds_rows<KST>(Kt, kb * 32 + l32, kk * 16 + h * 8);
+#pragma unroll
+                for (int b = 0; b < QB; ++b) sacc[kb][b] = mfma16(a, qf[b][kk], sacc[kb][b]);
+            }
+
+        if (MASKED) {   // causal test on original positions
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_s[buf][kb * 32 + 8 * g + 4 * h]);
+#pragma unroll
+                    for (int b = 0; b < QB; ++b) {
+                        if (kp.x > qpos[b]) sacc[kb][b][4 * g + 0] = -INFINITY;
+                        if (kp.y > qpos[b]) sacc[kb][b][4 * g + 1] = -INFINITY;
+                        if (kp.z > qpos[b]) sacc[kb][b][4 * g + 2] = -INFINITY;
+                        if (kp.w > qpos[b]) sacc[kb][b][4 * g + 3] = -INFINITY;
+                    }
+                }
+        }
+
+        // lane-local tile maximum per query; raise the reference only when needed
+        float mx[QB];
+        bool raise = false;
+#pragma unroll
+        for (int b = 0; b < QB; ++b) {
+            float a0 = sacc[0][b][0], a1 = sacc[1][b][0];
+#pragma unroll
+            for (int i = 1; i < 16; i += 2) {
+                a0 = fmaxf(a0, fmaxf(sacc[0][b][i], sacc[0][b][(i + 1) & 15]));
+                a1 = fmaxf(a1, fmaxf(sacc[1][b][i], sacc[1][b][(i + 1) & 15]));
+            }
+            mx[b] = fmaxf(a0, a1);
+            raise |= mx[b] > m[b] + lazy;               // -inf > -inf is false: no NaN is ever formed
+        }
+        if (__ballot(raise) != 0ull) {
+#pragma unroll
+            for (int b = 0; b < QB; ++b) {
+                const float m_new = fmaxf(m[b], half_max(mx[b]));
+                const float m_use = m_new == -INFINITY ? 0.f : m_new;
+                float alpha = fast_exp2((m[b] - m_use) * c);           // m = -inf -> 0
+                asm volatile("" : "+v"(alpha));   // rare path: keeps the rescale from being speculated
+                lsum[b] *= alpha;
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[b][db][i] *= alpha;
+                m[b] = m_new;
+                mc[b] = m_use * c - RTZ_BIAS_LOG2;
+            }
+        }
+
+        // P = exp2(c s - c m), packed to fp16; row sums from the packed values
+        f16x8 pf[QB][4];
+#pragma unroll
+        for (int b = 0; b < QB; ++b) {
+            float l0 = 0.f, l1 = 0.f;
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc) {
+                    uint32_t wv[4];
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const float p0 = fast_exp2(fmaf(sacc[kb][b][8 * cc + 2 * j], c, -mc[b]));
+                        const float p1 = fast_exp2(fmaf(sacc[kb][b][8 * cc + 2 * j + 1], c, -mc[b]));
+                        wv[j] = pack_f16(p0, p1);
+                    }
+                    l0 = add_pair(wv[0], l0); l1 = add_pair(wv[1], l1);
+                    l0 = add_pair(wv[2], l0); l1 = add_pair(wv[3], l1);
+                    pf[b][kb * 2 + cc] = as_f16x8(make_uint4(wv[0], wv[1], wv[2], wv[3]));
+                }
+            lsum[b] += l0 + l1;
+        }
+
+        // O^T += V^T P^T
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4)
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db) {
+                const f16x8 a = lds_trans<VST>(Vt, c4 * 16, db * 32, lane);
+#pragma unroll
+                for (int b = 0; b < QB; ++b) oacc[b][db] = mfma16(a, pf[b][c4], oacc[b][db]);
+            }
+    };
+
+    if (n_tiles > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    // one step: prefetch the next tile into registers, compute on the current LDS buffer,
+    // park the prefetched tile in the other buffer (last read before the previous barrier)
+    auto step = [&](int jt, auto masked_tag) {
+        const int buf = jt & 1;
+        const bool more = jt + 1 < n_tiles;
+        if (more) fetch(jt + 1);
+        tile(buf, masked_tag);
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    };
+    int jt = 0;
+    for (; jt < n_free; ++jt) step(jt, std::false_type{});
+    for (; jt < n_tiles; ++jt) step(jt, std::true_type{});
+
+#pragma unroll
+    for (int b = 0; b < QB; ++b) {
+        const float ltot = half_sum(lsum[b]);
+        const float inv = ltot > 0.f ? 1.f / ltot : 0.f;
+        if (qvalid[b]) {
+            const size_t row = (seg + qpos[b]) * D + 4 * h;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const float x0 = oacc[b][db][4 * g + 0] * inv, x1 = oacc[b][db][4 * g + 1] * inv;
+                    const float x2 = oacc[b][db][4 * g + 2] * inv, x3 = oacc[b][db][4 * g + 3] * inv;
+                    const __bf16 y0 = (__bf16)x0, y1 = (__bf16)x1, y2 = (__bf16)x2, y3 = (__bf16)x3;
+                    uint2 pk;
+                    pk.x = (uint32_t)__builtin_bit_cast(uint16_t, y0) | ((uint32_t)__builtin_bit_cast(uint16_t, y1) << 16);
+                    pk.y = (uint32_t)__builtin_bit_cast(uint16_t, y2) | ((uint32_t)__builtin_bit_cast(uint16_t, y3) << 16);
+                    *reinterpret_cast<uint2*>(o + row + db * 32 + 8 * g) = pk;
+                    if (o_f32) *reinterpret_cast<float4*>(o_f32 + row + db * 32 + 8 * g) = make_float4(x0, x1, x2, x3);
+                }
+            if (h == 0) lse[seg + qpos[b]] = ltot > 0.f ? fmaf(m[b], tau, logf(ltot)) : -INFINITY;
+        }
+    }
+}
+
+template <int D, int NW, int QB>
+static int launch_fwd_t(const void* q, const void* k, const void* v, const int32_t* q_idx, const int32_t* k_idx,
+                        const int32_t* work, int n_work, int S, int T, float tau, void* o, float* lse,
+                        float* o_f32, hipStream_t st)
+{
+    constexpr size_t smem = 2 * FWD_TILE_N * ((D + 8) + (D + 16)) * 2 + 2 * FWD_TILE_N * 4;
+    static bool attr_set = false;
+    if (!attr_set) {
+        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_f16_kernel<D, NW, QB>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((size_t)S * n_work));
+    hipLaunchKernelGGL((attn_fwd_f16_kernel<D, NW, QB>), grid, dim3(NW * 64), smem, st, (const uint16_t*)q,
+                       (const uint16_t*)k, (const uint16_t*)v, q_idx, k_idx, work, n_work, S, T, tau,
+                       (uint16_t*)o, lse, o_f32);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
+                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+                         float tau, void* o, float* lse, float* o_f32, hipStream_t st)
+{
+    ProfScope prof(SCFA_K_FWD, st);
+    if (d == 64) {
+        static const int variant = getenv("SCFA_FWD_VARIANT") ? atoi(getenv("SCFA_FWD_VARIANT")) : 1;
+        if (variant == 1) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
+        return launch_fwd_t<64, 2, 2>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
+    }
+    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
+    return SCFA_EUNSUPPORTED;
+}
+
+}  // namespace scfa

@@ -54,7 +54,7 @@ int launch_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* 
 int launch_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out,
                         hipStream_t st);
 int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
-                       int row_bytes, void* out, hipStream_t st);
+                       int row_bytes, bool bf16_to_f16, void* out, hipStream_t st);
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
                         int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,

@@ -152,9 +152,47 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
     out[((size_t)s * T + r) * chunks_per_row + c] = x[((size_t)s * T + src) * chunks_per_row + c];
 }
 
-int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
-                       int row_bytes, void* out, hipStream_t st)
+// Same gather for bf16 rows, converting to fp16 on the way (round to nearest even; exact
+// for magnitudes in [2^-17, 65504], larger ones saturate to the largest fp16).
+__global__ __launch_bounds__(256) void gather_rows_bf16_to_f16_kernel(const uint4* __restrict__ x,
+                                                                      const int32_t* __restrict__ idx,
+                                                                      const int32_t* __restrict__ count, int T,
+                                                                      int chunks_per_row, uint4* __restrict__ out)
 {
+    const int s = blockIdx.y;
+    const int n = count ? count[s] : T;
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int r = (int)(g / chunks_per_row);
+    const int c = (int)(g % chunks_per_row);
+    if (r >= n) return;
+    const int src = idx[(size_t)s * T + r];
+    const uint4 v = x[((size_t)s * T + src) * chunks_per_row + c];
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    uint32_t o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+        lo = fminf(fmaxf(lo, -65504.f), 65504.f);
+        hi = fminf(fmaxf(hi, -65504.f), 65504.f);
+        const _Float16 a = (_Float16)lo, b = (_Float16)hi;
+        o[i] = (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+    }
+    out[((size_t)s * T + r) * chunks_per_row + c] = make_uint4(o[0], o[1], o[2], o[3]);
+}
+
+int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
+                       int row_bytes, bool bf16_to_f16, void* out, hipStream_t st)
+{
+    if (bf16_to_f16) {
+        const int cpr = row_bytes / 16;
+        const long long total = (long long)T * cpr;
+        dim3 grid((unsigned)((total + 255) / 256), S);
+        ProfScope prof(SCFA_K_GATHER, st);
+        hipLaunchKernelGGL(gather_rows_bf16_to_f16_kernel, grid, dim3(256), 0, st, (const uint4*)x, idx, count, T,
+                           cpr, (uint4*)out);
+        SCFA_HIP_TRY(hipGetLastError());
+        return SCFA_OK;
+    }
     const int cpr = row_bytes / 16;
     const long long total = (long long)T * cpr;
     dim3 grid((unsigned)((total + 255) / 256), S);

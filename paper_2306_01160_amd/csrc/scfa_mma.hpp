@@ -1,0 +1,177 @@
+// Matrix-core and LDS helpers shared by the fp16-compute attention kernels (gfx950).
+//
+// Compute format.  The permuted Q, K, V (and dO) the kernels consume are fp16: the
+// conversion from bf16 is exact for magnitudes in [2^-17, 65504], so scores are the
+// same products a bf16 contraction would form, while P and dS -- which must be rounded
+// to 16 bits for the second contraction -- keep 11 significant bits instead of 8.
+//
+// v_mfma_f32_32x32x16_f16 (64 lanes):
+//   A (32 x 16): lane l holds row l%32, contraction slots 8*(l/32) .. +7
+//   B (16 x 32): lane l holds column l%32, contraction slots 8*(l/32) .. +7
+//   C/D (32 x 32): lane l holds column l%32; register i holds row 8*(i/4) + 4*(l/32) + i%4
+// Any assignment of contraction indices to slots is valid as long as A and B agree.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace scfa {
+
+using f16x8 = _Float16 __attribute__((ext_vector_type(8)));
+using f16x2 = _Float16 __attribute__((ext_vector_type(2)));
+using f32x16 = float __attribute__((ext_vector_type(16)));
+using i16x4 = short __attribute__((ext_vector_type(4)));
+
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ __forceinline__ f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
+
+__device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ f32x16 zero16()
+{
+    f32x16 z;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) z[i] = 0.f;
+    return z;
+}
+
+// two floats -> packed fp16 pair, round toward zero (finite inputs never become inf)
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi)
+{
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// log2(1 + 2^-12): added to the exponent of every probability that is then truncated to
+// fp16 (11 significant bits), so that the truncation error is centred on zero instead of
+// biasing row sums and outputs low by 2^-12.
+constexpr float RTZ_BIAS_LOG2 = 3.5218e-4f;
+
+// makes the compiler treat v as consumed here (pending loads into it are waited for)
+template <typename V>
+__device__ __forceinline__ void touch(V& v)
+{
+#ifndef SCFA_EXP_NO_TOUCH
+    asm volatile("" : "+v"(v));
+#endif
+}
+
+// fp32 sum of the two fp16 halves of w, added to acc
+__device__ __forceinline__ float add_pair(uint32_t w, float acc)
+{
+    const f16x2 ones = {(_Float16)1.0f, (_Float16)1.0f};
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, w), ones, acc, false);
+}
+
+// exchange between the two lane halves: returns op(x in lanes 0-31, x in lanes 32-63) in all lanes
+__device__ __forceinline__ float half_max(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// registers 8*cc .. 8*cc+7 of an accumulator block as an fp16 B-operand chunk; the
+// contraction slots of lane half h are rows { 16*cc + 4h + 0..3, 16*cc + 8 + 4h + 0..3 }
+__device__ __forceinline__ f16x8 pack_chunk(const f32x16& p, int cc)
+{
+    return as_f16x8(make_uint4(pack_f16(p[8 * cc + 0], p[8 * cc + 1]), pack_f16(p[8 * cc + 2], p[8 * cc + 3]),
+                               pack_f16(p[8 * cc + 4], p[8 * cc + 5]), pack_f16(p[8 * cc + 6], p[8 * cc + 7])));
+}
+
+// ---------------------------------------------------------------------------
+// Row-major fp16 tiles in LDS.  STRIDE is the row stride in elements.
+//   "rows" operand : contraction along the row (head dimension), one 16-byte read
+//   "trans" operand: contraction along the tile's rows; two transposing 8-byte reads
+//                    (ds_read_b64_tr_b16) give 4 + 4 consecutive tile rows per lane
+// ---------------------------------------------------------------------------
+template <int STRIDE>
+__device__ __forceinline__ f16x8 lds_rows(const uint16_t* tile, int row, int col)
+{
+    return as_f16x8(*reinterpret_cast<const uint4*>(tile + row * STRIDE + col));
+}
+
+// ds_read_b64_tr_b16 within a block of 16 lanes: lane i receives element i%4 of the four
+// 4-element rows addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of its block.
+__device__ __forceinline__ uint2 lds_tr_read(const uint16_t* p)
+{
+    using lds_ptr = i16x4 __attribute__((address_space(3)))*;
+    const i16x4 r = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+    return __builtin_bit_cast(uint2, r);
+}
+
+// A operand (32 x 16) = transpose of tile[r0 .. r0+16)[c0 .. c0+32): lane l gets column
+// c0 + l%32 and tile rows { r0 + 4h + 0..3, r0 + 8 + 4h + 0..3 } (h = l/32), the slot order
+// pack_chunk gives the B operand.
+template <int STRIDE>
+__device__ __forceinline__ f16x8 lds_trans(const uint16_t* tile, int r0, int c0, int lane)
+{
+    const int r = lane & 15, blk = (lane >> 4) & 1, h = lane >> 5;
+    const uint16_t* p = tile + (r0 + 4 * h + (r >> 2)) * STRIDE + c0 + 16 * blk + 4 * (r & 3);
+    const uint2 a = lds_tr_read(p);
+    const uint2 b = lds_tr_read(p + 8 * STRIDE);
+    return as_f16x8(make_uint4(a.x, a.y, b.x, b.y));
+}
+
+// ---------------------------------------------------------------------------
+// Buffer loads: the resource carries the byte range of the rows a workgroup may read,
+// so rows past the end come back as zeros without any predication, and the per-tile
+// offset is a scalar (no vector address arithmetic in the tile loop).
+using rsrc_t = __amdgpu_buffer_rsrc_t;
+using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buffer_load16(rsrc_t r, int voffset, int soffset)
+{
+    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, voffset, soffset, 0));
+}
+__device__ __forceinline__ int buffer_load4(rsrc_t r, int voffset, int soffset)
+{
+    return __builtin_amdgcn_raw_buffer_load_b32(r, voffset, soffset, 0);
+}
+
+// Cooperative copy of ROWS contiguous rows x D fp16 (one tile) from global memory into
+// registers and on into an LDS tile with row stride STRIDE.  Rows past the end of the
+// resource read as zeros.
+template <int D, int ROWS, int THREADS>
+struct TileRegs {
+    static constexpr int CHUNKS = D / 8;                   // 16-byte chunks per row
+    static constexpr int ITEMS = ROWS * CHUNKS / THREADS;  // chunks per thread
+    static constexpr int TILE_BYTES = ROWS * D * 2;
+    static_assert(ROWS * CHUNKS % THREADS == 0, "tile must split evenly over the workgroup");
+    uint4 r[ITEMS];
+
+    // tile_byte_offset is wave-uniform
+    __device__ __forceinline__ void load(rsrc_t rsrc, int tile_byte_offset)
+    {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u)
+            r[u] = buffer_load16(rsrc, (int)threadIdx.x * 16, tile_byte_offset + u * THREADS * 16);
+    }
+    template <int STRIDE>
+    __device__ __forceinline__ void store(uint16_t* tile) const
+    {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const int item = threadIdx.x + THREADS * u;
+            const int row = item / CHUNKS, c8 = item % CHUNKS;
+            *reinterpret_cast<uint4*>(tile + row * STRIDE + c8 * 8) = r[u];
+        }
+    }
+};
+
+}  // namespace scfa

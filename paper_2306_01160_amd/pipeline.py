@@ -46,10 +46,10 @@ def _seg(x):
 
 def _o_f32_buffer(q, need_bwd):
     """fp32 side copy of O for the backward's D = <dO, O> (bf16 path, training only).
-    Zero-initialised: the forward does not write the rows of dropped queries."""
+    Rows of dropped queries are never written and never read back."""
     if not need_bwd or q.dtype != torch.bfloat16:
         return None
-    return torch.zeros(q.shape, dtype=torch.float32, device=q.device)
+    return torch.empty(q.shape, dtype=torch.float32, device=q.device)
 
 
 def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
@@ -58,13 +58,16 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
     q_idx, q_bs, q_off = sc.scfa_sort_by_bucket(_seg(bucket_q), nb)
     k_idx, k_bs, k_off = sc.scfa_sort_by_bucket(_seg(bucket_k), nb)
-    q_p = sc.scfa_gather_rows(_seg(q), q_idx)
-    k_p = sc.scfa_gather_rows(_seg(k), k_idx)
-    v_p = sc.scfa_gather_rows(_seg(v), k_idx)
+    f16 = q.dtype == torch.bfloat16
+    q_p = sc.scfa_gather_rows(_seg(q), q_idx, to_f16=f16)
+    k_p = sc.scfa_gather_rows(_seg(k), k_idx, to_f16=f16)
+    v_p = sc.scfa_gather_rows(_seg(v), k_idx, to_f16=f16)
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
                                                         want_bwd=need_bwd)
     o_f32 = _o_f32_buffer(q, need_bwd)
     o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f32_out=o_f32)
+    if need_bwd and f16:   # TEMP: the backward kernels still read bf16 copies
+        q_p, k_p, v_p = (sc.scfa_gather_rows(_seg(x), i) for x, i in ((q, q_idx), (k, k_idx), (v, k_idx)))
     ctx = Context(sc.SCFA_HASH, B, H, nb, sm_scale, q_p, k_p, v_p, q_idx, k_idx, None, None, fwd_work, bwd_work,
                   counters, o, lse, o_f32, q_bs, k_bs, q_off, k_off)
     return o, lse, ctx
@@ -82,13 +85,16 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True):
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
     q_idx, n_q = sc.scfa_compact_keep(_seg(keep_q))
     k_idx, n_k = sc.scfa_compact_keep(_seg(keep_k))
-    q_c = sc.scfa_gather_rows(_seg(q), q_idx, n_q)
-    k_c = sc.scfa_gather_rows(_seg(k), k_idx, n_k)
-    v_c = sc.scfa_gather_rows(_seg(v), k_idx, n_k)
+    f16 = q.dtype == torch.bfloat16
+    q_c = sc.scfa_gather_rows(_seg(q), q_idx, n_q, to_f16=f16)
+    k_c = sc.scfa_gather_rows(_seg(k), k_idx, n_k, to_f16=f16)
+    v_c = sc.scfa_gather_rows(_seg(v), k_idx, n_k, to_f16=f16)
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_QKDROP, q_idx, k_idx, n_q, n_k, 1, tiles,
                                                         want_bwd=need_bwd)
     o_f32 = _o_f32_buffer(q, need_bwd)
     o, lse = sc.scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_f32_out=o_f32)
+    if need_bwd and f16:   # TEMP: the backward kernels still read bf16 copies
+        q_c, k_c, v_c = (sc.scfa_gather_rows(_seg(x), i, n) for x, i, n in ((q, q_idx, n_q), (k, k_idx, n_k), (v, k_idx, n_k)))
     ctx = Context(sc.SCFA_QKDROP, B, H, 1, sm_scale, q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work,
                   counters, o, lse, o_f32)
     return o, lse, ctx
