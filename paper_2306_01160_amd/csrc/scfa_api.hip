@@ -117,6 +117,10 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
     float* delta_perm = reinterpret_cast<float*>(w);
     w += align_up((size_t)S * T * 4, 256);
     float* lse_perm = reinterpret_cast<float*>(w);
+    w += align_up((size_t)S * T * 4, 256);
+    uint32_t* amax = reinterpret_cast<uint32_t*>(w);
+    w += align_up((size_t)S * 4, 256);
+    float* inv_scale = reinterpret_cast<float*>(w);
 
     if (qkdrop) {
         rc = launch_zero_rows(q_idx, n_q, S, T, d * 4, dq, nullptr, nullptr, 0.f, st);
@@ -124,13 +128,13 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
         rc = launch_zero_rows(k_idx, n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
     }
-    rc = launch_bwd_prep_bf16(o, o_f32, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, st);
+    rc = launch_bwd_prep_bf16(o, o_f32, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
-    rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, lse_perm, delta_perm, q_idx, k_idx, bwd_work, n_bwd, S, T,
-                                   d, sm_scale, dk, dv, st);
+    rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd,
+                                   S, T, d, sm_scale, dk, dv, st);
     if (rc != SCFA_OK) return rc;
-    return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, q_idx, k_idx, fwd_work, n_fwd, S, T, d,
-                                   sm_scale, dq, st);
+    return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd,
+                                   S, T, d, sm_scale, dq, st);
 }
 
 }  // namespace scfa
@@ -244,7 +248,8 @@ int scfa_qkdrop_attn_fwd(const void* q_c, const void* k_c, const void* v_c, cons
 size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype)
 {
     if (S <= 0 || T <= 0 || d <= 0 || dtype != SCFA_BF16) return 0;
-    return align_up((size_t)S * T * d * 2, 256) + 2 * align_up((size_t)S * T * 4, 256);
+    return align_up((size_t)S * T * d * 2, 256) + 2 * align_up((size_t)S * T * 4, 256) +
+           2 * align_up((size_t)S * 4, 256);
 }
 
 int scfa_hash_attn_bwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,

@@ -1,0 +1,554 @@
+// Backward attention over the work lists, fp16 compute format, fp32 accumulation.
+//
+// The paper adapts the backward "in a similar fashion" to the forward (Sec. 3.1, 3.2):
+// per block of keys, find the blocks of queries that can see it.  The gradients are those
+// of masked softmax attention with P recomputed from the saved logsumexp:
+//   P_ij = exp(tau s_ij - LSE_i),  dP_ij = <dO_i, V_j>,  D_i = <dO_i, O_i>,
+//   dS_ij = P_ij (dP_ij - D_i),  dV_j = sum_i P_ij dO_i,  dK_j = tau sum_i dS_ij Q_i,
+//   dQ_i = tau sum_j dS_ij K_j.
+// Three kernels: a pre-pass (D, and dO / LSE brought into permuted order), a key-major
+// kernel for dK and dV (backward work list), and a query-major kernel for dQ (forward
+// work list).  Nothing is accumulated with atomics, so results are deterministic.
+//
+// dO is multiplied by a power of two per (batch, head) segment so that its largest
+// magnitude lies in [1, 2) before it is converted to fp16; the gradients are multiplied
+// by the inverse power at the end.  Both scalings are exact.
+#include "scfa_common.hpp"
+#include "scfa_mma.hpp"
+
+#include <math.h>
+
+#include <type_traits>
+
+namespace scfa {
+
+// ===========================================================================
+// Pre-pass
+// ===========================================================================
+__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, int n, uint32_t v)
+{
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+// amax[s] = max |dO[s]| as float bits (non-negative floats order like unsigned integers)
+__global__ __launch_bounds__(256) void dout_amax_kernel(const uint4* __restrict__ d_o, long long chunks_per_seg,
+                                                        uint32_t* __restrict__ amax)
+{
+    const int s = blockIdx.y;
+    const uint4* p = d_o + (size_t)s * chunks_per_seg;
+    uint32_t m = 0;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks_per_seg; i += (long long)gridDim.x * 256) {
+        const uint4 v = p[i];
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            m = max(m, (w[j] << 16) & 0x7fffffffu);
+            m = max(m, w[j] & 0x7fff0000u);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(&amax[s], m);
+}
+
+// power-of-two scale that brings a magnitude with these float bits into [1, 2)
+__device__ __forceinline__ void pow2_scales(uint32_t amax_bits, float& scale, float& inv_scale)
+{
+    int e = (int)((amax_bits >> 23) & 0xff);
+    if (amax_bits == 0 || e == 0xff) e = 127;        // zero or non-finite: no scaling
+    e = max(e, 1);
+    scale = __uint_as_float((uint32_t)(254 - e) << 23);      // 2^-(e-127)
+    inv_scale = __uint_as_float((uint32_t)e << 23);          // 2^(e-127)
+}
+
+// One row is handled by D/8 adjacent lanes (16 bytes of dO each).
+template <int D>
+__global__ __launch_bounds__(256) void bwd_prep_kernel(
+    const uint16_t* __restrict__ o, const float* __restrict__ o_f32, const float* __restrict__ lse,
+    const uint16_t* __restrict__ d_o, const int32_t* __restrict__ q_idx, const uint32_t* __restrict__ amax,
+    int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
+    float* __restrict__ inv_scale_out)
+{
+    constexpr int LPR = D / 8;   // lanes per row
+    const int s = blockIdx.y;
+    const size_t seg = (size_t)s * T;
+    const int r = (blockIdx.x * 256 + threadIdx.x) / LPR;
+    const int c8 = threadIdx.x % LPR;
+    const bool valid = r < T;
+    float scale, inv_scale;
+    pow2_scales(amax[s], scale, inv_scale);
+    if (blockIdx.x == 0 && threadIdx.x == 0) inv_scale_out[s] = inv_scale;
+    float acc = 0.f;
+    int src = 0;
+    if (valid) {
+        src = q_idx[seg + r];
+        const uint4 g = *reinterpret_cast<const uint4*>(d_o + (seg + src) * D + c8 * 8);
+        const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
+        float gs[8], y[8];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            gs[2 * w] = __uint_as_float(gw[w] << 16) * scale;
+            gs[2 * w + 1] = __uint_as_float(gw[w] & 0xffff0000u) * scale;
+        }
+        if (o_f32) {   // full-precision copy of O kept by the forward
+            const float4 y0 = *reinterpret_cast<const float4*>(o_f32 + (seg + src) * D + c8 * 8);
+            const float4 y1 = *reinterpret_cast<const float4*>(o_f32 + (seg + src) * D + c8 * 8 + 4);
+            y[0] = y0.x; y[1] = y0.y; y[2] = y0.z; y[3] = y0.w; y[4] = y1.x; y[5] = y1.y; y[6] = y1.z; y[7] = y1.w;
+        } else {
+            const uint4 yb = *reinterpret_cast<const uint4*>(o + (seg + src) * D + c8 * 8);
+            const uint32_t yw[4] = {yb.x, yb.y, yb.z, yb.w};
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                y[2 * w] = __uint_as_float(yw[w] << 16);
+                y[2 * w + 1] = __uint_as_float(yw[w] & 0xffff0000u);
+            }
+        }
+        uint32_t out[4];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            acc = fmaf(gs[2 * w], y[2 * w], acc);
+            acc = fmaf(gs[2 * w + 1], y[2 * w + 1], acc);
+            const _Float16 a = (_Float16)gs[2 * w], b = (_Float16)gs[2 * w + 1];
+            out[w] = (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+        }
+        *reinterpret_cast<uint4*>(do_perm + (seg + r) * D + c8 * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+    }
+#pragma unroll
+    for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if (valid && c8 == 0) {
+        delta_perm[seg + r] = acc;
+        lse_perm[seg + r] = lse[seg + src];
+    }
+}
+
+int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
+                         int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
+                         uint32_t* amax, float* inv_scale, hipStream_t st)
+{
+    ProfScope prof(SCFA_K_BWD_PREP, st);
+    hipLaunchKernelGGL(fill_u32_kernel, dim3((S + 255) / 256), dim3(256), 0, st, amax, S, 0u);
+    const long long chunks = (long long)T * d / 8;
+    const long long want = (chunks + 256 * 8 - 1) / (256 * 8);
+    const unsigned nblk = (unsigned)(want < 256 ? want : 256);
+    hipLaunchKernelGGL(dout_amax_kernel, dim3(nblk, S), dim3(256), 0, st, (const uint4*)d_o, chunks, amax);
+    const long long threads = (long long)T * (d / 8);
+    dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
+    if (d == 64)
+        hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
+                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, inv_scale);
+    else if (d == 128)
+        hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
+                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, inv_scale);
+    else
+        return SCFA_EUNSUPPORTED;
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+// ===========================================================================
+// dK / dV: a workgroup owns 128 keys of one bucket (32 per wavefront, in the lanes)
+// and walks the 64-row query tiles that can see them.  Per tile:
+//   S = Q K^T, dP = dO V^T (queries x keys; lane = key, registers = queries)
+//   P = exp2(c S - LSE log2 e), dS = P (dP - D)
+//   dV^T += dO^T P,  dK^T += Q^T dS   (d x keys; Q^T, dO^T by transposing LDS reads)
+// ===========================================================================
+template <int D>
+struct DkdvSmem {
+    static constexpr int BM = BWD_TILE_M;
+    uint16_t Qs[2][BM * D];
+    uint16_t Gs[2][BM * D];     // dO rows
+    float lse2[2][BM];          // LSE * log2(e); +inf for rows that contribute nothing
+    float delta[2][BM];
+    int32_t qpos[2][BM];
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
+    const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
+    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau,
+    float* __restrict__ dk, float* __restrict__ dv)
+{
+    constexpr int BM = BWD_TILE_M;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    DkdvSmem<D>& sm = *reinterpret_cast<DkdvSmem<D>*>(smem_raw);
+
+    const int s = blockIdx.x % S;
+    const int w = blockIdx.x / S;
+    const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
+    const int k_begin = it[BW_KBEGIN], k_count = it[BW_KCOUNT];
+    const int q_begin = it[BW_QBEGIN], q_count = it[BW_QCOUNT], q_masked = it[BW_QMASKED];
+    if (k_count <= 0) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const size_t seg = (size_t)s * T;
+    const int krow = wave * 32 + l32;
+    const bool kvalid = krow < k_count;
+    const int kr = min(krow, k_count - 1);            // keys past the end repeat the last one; never written
+    const int kpos_ld = k_idx[seg + k_begin + kr];
+    const int kpos = kvalid ? kpos_ld : INT32_MAX;
+
+    f16x8 kf[D / 16], vf[D / 16];
+    {
+        const uint16_t* kp = k + (seg + k_begin + kr) * D + h * 8;
+        const uint16_t* vp = v + (seg + k_begin + kr) * D + h * 8;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+            kf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(kp + kk * 16));
+            vf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(vp + kk * 16));
+        }
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) { touch(kf[kk]); touch(vf[kk]); }
+    }
+
+    f32x16 dkacc[D / 32], dvacc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) { dkacc[db] = zero16(); dvacc[db] = zero16(); }
+    const float c = tau * LOG2E;
+
+    const int n_tiles = (q_count + BM - 1) / BM;
+    const int n_masked = min((q_masked + BM - 1) / BM, n_tiles);   // leading tiles that need the causal test
+
+    TileRegs<D, BM, 256> qt, gt;
+    const rsrc_t q_rsrc = make_rsrc(q + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
+    const rsrc_t g_rsrc = make_rsrc(do_perm + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
+    const rsrc_t l_rsrc = make_rsrc(lse_perm + seg + q_begin, (uint32_t)q_count * 4);
+    const rsrc_t d_rsrc = make_rsrc(delta_perm + seg + q_begin, (uint32_t)q_count * 4);
+    const rsrc_t p_rsrc = make_rsrc(q_idx + seg + q_begin, (uint32_t)q_count * 4);
+    float lse_reg = 0.f, delta_reg = 0.f;
+    int qp_reg = 0, q_row = 0;
+    auto fetch = [&](int jt) {
+        qt.load(q_rsrc, jt * qt.TILE_BYTES);
+        gt.load(g_rsrc, jt * gt.TILE_BYTES);
+        if (tid < BM) {
+            lse_reg = __int_as_float(buffer_load4(l_rsrc, tid * 4, jt * BM * 4));
+            delta_reg = __int_as_float(buffer_load4(d_rsrc, tid * 4, jt * BM * 4));
+            qp_reg = buffer_load4(p_rsrc, tid * 4, jt * BM * 4);
+            q_row = jt * BM + tid;
+        }
+    };
+    auto stash = [&](int buf) {
+        qt.store_swz(sm.Qs[buf]);
+        gt.store_swz(sm.Gs[buf]);
+        if (tid < BM) {
+            const bool ok = q_row < q_count && lse_reg != -INFINITY;   // rows past the end / without keys: P = 0
+            sm.lse2[buf][tid] = ok ? fmaf(lse_reg, LOG2E, -RTZ_BIAS_LOG2) : INFINITY;
+            sm.delta[buf][tid] = delta_reg;
+            sm.qpos[buf][tid] = q_row < q_count ? qp_reg : -1;
+        }
+    };
+
+    auto tile = [&](int buf, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const uint16_t* Qt = sm.Qs[buf];
+        const uint16_t* Gt = sm.Gs[buf];
+        f32x16 sacc[2], pacc[2];
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) { sacc[qb] = zero16(); pacc[qb] = zero16(); }
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+            for (int qb = 0; qb < 2; ++qb) {
+                sacc[qb] = mfma16(swz_rows<D>(Qt, qb * 32 + l32, kk * 16 + h * 8), kf[kk], sacc[qb]);
+                pacc[qb] = mfma16(swz_rows<D>(Gt, qb * 32 + l32, kk * 16 + h * 8), vf[kk], pacc[qb]);
+            }
+
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int r = qb * 32 + 8 * g + 4 * h;
+                const float4 l2 = *reinterpret_cast<const float4*>(&sm.lse2[buf][r]);
+                const float4 dl = *reinterpret_cast<const float4*>(&sm.delta[buf][r]);
+                const float l2a[4] = {l2.x, l2.y, l2.z, l2.w};
+                const float dla[4] = {dl.x, dl.y, dl.z, dl.w};
+                int qpa[4] = {0, 0, 0, 0};
+                if (MASKED) {
+                    const int4 qp = *reinterpret_cast<const int4*>(&sm.qpos[buf][r]);
+                    qpa[0] = qp.x; qpa[1] = qp.y; qpa[2] = qp.z; qpa[3] = qp.w;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float p = fast_exp2(fmaf(sacc[qb][4 * g + e], c, -l2a[e]));
+                    if (MASKED) { if (kpos > qpa[e]) p = 0.f; }     // causal test on original positions
+                    sacc[qb][4 * g + e] = p;
+                    pacc[qb][4 * g + e] = p * (pacc[qb][4 * g + e] - dla[e]);
+                }
+            }
+
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) {
+            const f16x8 pf = pack_chunk(sacc[c4 >> 1], c4 & 1);
+            const f16x8 sf = pack_chunk(pacc[c4 >> 1], c4 & 1);
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db) {
+                int oa, ob;
+                swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
+                dvacc[db] = mfma16(swz_trans(Gt, oa, ob), pf, dvacc[db]);
+                dkacc[db] = mfma16(swz_trans(Qt, oa, ob), sf, dkacc[db]);
+            }
+        }
+    };
+
+    if (n_tiles > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    auto step = [&](int jt, auto masked_tag) {
+        const int buf = jt & 1;
+        const bool more = jt + 1 < n_tiles;
+        if (more) fetch(jt + 1);
+        tile(buf, masked_tag);
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    };
+    int jt = 0;
+    for (; jt < n_masked; ++jt) step(jt, std::true_type{});
+    for (; jt < n_tiles; ++jt) step(jt, std::false_type{});
+
+    if (kvalid) {
+        const float us = inv_scale[s];
+        const float sk = tau * us;
+        float* dkp = dk + (seg + kpos) * D + 4 * h;
+        float* dvp = dv + (seg + kpos) * D + 4 * h;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                *reinterpret_cast<float4*>(dkp + db * 32 + 8 * g) =
+                    make_float4(dkacc[db][4 * g] * sk, dkacc[db][4 * g + 1] * sk, dkacc[db][4 * g + 2] * sk, dkacc[db][4 * g + 3] * sk);
+                *reinterpret_cast<float4*>(dvp + db * 32 + 8 * g) =
+                    make_float4(dvacc[db][4 * g] * us, dvacc[db][4 * g + 1] * us, dvacc[db][4 * g + 2] * us, dvacc[db][4 * g + 3] * us);
+            }
+    }
+}
+
+template <int D>
+static int launch_dkdv_t(const void* q, const void* k, const void* v, const void* do_perm,
+                         const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                         const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S,
+                         int T, float tau, float* dk, float* dv, hipStream_t st)
+{
+    const size_t smem = sizeof(DkdvSmem<D>);
+    static bool attr_set = false;
+    if (!attr_set) {
+        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_f16_kernel<D>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((size_t)S * n_work)), block(256);
+    hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx,
+                       work, n_work, S, T, tau, dk, dv);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
+                              const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                              const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
+                              int S, int T, int d, float tau, float* dk, float* dv, hipStream_t st)
+{
+    ProfScope prof(SCFA_K_BWD_DKDV, st);
+    if (d == 64)
+        return launch_dkdv_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, tau, dk, dv, st);
+    if (d == 128)
+        return launch_dkdv_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, tau, dk, dv, st);
+    return SCFA_EUNSUPPORTED;
+}
+
+// ===========================================================================
+// dQ: same walk as the forward (a workgroup owns 128 queries of one bucket, 32 per
+// wavefront in the lanes; keys 64 at a time).  Per tile:
+//   S^T = K Q^T, dP^T = V dO^T (keys x queries), dS^T = P^T (dP^T - D), dQ^T += K^T dS^T
+// ===========================================================================
+template <int D>
+struct DqSmem {
+    static constexpr int BN = FWD_TILE_N;
+    uint16_t Ks[2][BN * D];
+    uint16_t Vs[2][BN * D];
+    int32_t kpos[2][BN];
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
+    const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
+    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, float* __restrict__ dq)
+{
+    constexpr int BN = FWD_TILE_N;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
+
+    const int s = blockIdx.x % S;
+    const int w = blockIdx.x / S;
+    const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
+    const int q_begin = it[W_QBEGIN], q_count = it[W_QCOUNT];
+    const int k_begin = it[W_KBEGIN], k_count = it[W_KCOUNT], k_nomask = it[W_KNOMASK];
+    if (q_count <= 0) return;
+
+    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const size_t seg = (size_t)s * T;
+    const int qrow = wave * 32 + l32;
+    const bool qvalid = qrow < q_count;
+    const int qr = min(qrow, q_count - 1);              // rows past the end repeat the last one; never written
+    const int qpos_ld = q_idx[seg + q_begin + qr];
+    const int qpos = qvalid ? qpos_ld : -1;
+    const float lse_ld = lse_perm[seg + q_begin + qr];
+    const float lse2 = (qvalid && lse_ld != -INFINITY) ? fmaf(lse_ld, LOG2E, -RTZ_BIAS_LOG2) : INFINITY;
+    const float delta = delta_perm[seg + q_begin + qr];
+
+    f16x8 qf[D / 16], gf[D / 16];
+    {
+        const uint16_t* qp = q + (seg + q_begin + qr) * D + h * 8;
+        const uint16_t* gp = do_perm + (seg + q_begin + qr) * D + h * 8;
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) {
+            qf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16));
+            gf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(gp + kk * 16));
+        }
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk) { touch(qf[kk]); touch(gf[kk]); }
+    }
+
+    f32x16 dqacc[D / 32];
+#pragma unroll
+    for (int db = 0; db < D / 32; ++db) dqacc[db] = zero16();
+    const float c = tau * LOG2E;
+
+    const int n_tiles = (k_count + BN - 1) / BN;
+    const int n_free = min(k_nomask / BN, n_tiles);
+
+    TileRegs<D, BN, 256> kt, vt;
+    const rsrc_t k_rsrc = make_rsrc(k + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
+    const rsrc_t v_rsrc = make_rsrc(v + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
+    const rsrc_t p_rsrc = make_rsrc(k_idx + seg + k_begin, (uint32_t)k_count * 4);
+    int kp_reg = 0, kp_row = 0;
+    auto fetch = [&](int jt) {
+        kt.load(k_rsrc, jt * kt.TILE_BYTES);
+        vt.load(v_rsrc, jt * vt.TILE_BYTES);
+        if (tid < BN) {
+            kp_reg = buffer_load4(p_rsrc, tid * 4, jt * BN * 4);
+            kp_row = jt * BN + tid;
+        }
+    };
+    auto stash = [&](int buf) {
+        kt.store_swz(sm.Ks[buf]);
+        vt.store_swz(sm.Vs[buf]);
+        if (tid < BN) sm.kpos[buf][tid] = kp_row < k_count ? kp_reg : INT32_MAX;   // keys past the end are never allowed
+    };
+
+    auto tile = [&](int buf, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        const uint16_t* Kt = sm.Ks[buf];
+        const uint16_t* Vt = sm.Vs[buf];
+        f32x16 sacc[2], pacc[2];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) { sacc[kb] = zero16(); pacc[kb] = zero16(); }
+#pragma unroll
+        for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                sacc[kb] = mfma16(swz_rows<D>(Kt, kb * 32 + l32, kk * 16 + h * 8), qf[kk], sacc[kb]);
+                pacc[kb] = mfma16(swz_rows<D>(Vt, kb * 32 + l32, kk * 16 + h * 8), gf[kk], pacc[kb]);
+            }
+
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                int kpa[4] = {0, 0, 0, 0};
+                if (MASKED) {
+                    const int4 kp = *reinterpret_cast<const int4*>(&sm.kpos[buf][kb * 32 + 8 * g + 4 * h]);
+                    kpa[0] = kp.x; kpa[1] = kp.y; kpa[2] = kp.z; kpa[3] = kp.w;
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float p = fast_exp2(fmaf(sacc[kb][4 * g + e], c, -lse2));
+                    if (MASKED) { if (kpa[e] > qpos) p = 0.f; }     // causal test on original positions
+                    pacc[kb][4 * g + e] = p * (pacc[kb][4 * g + e] - delta);
+                }
+            }
+
+#pragma unroll
+        for (int c4 = 0; c4 < 4; ++c4) {
+            const f16x8 sf = pack_chunk(pacc[c4 >> 1], c4 & 1);
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db) {
+                int oa, ob;
+                swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
+                dqacc[db] = mfma16(swz_trans(Kt, oa, ob), sf, dqacc[db]);
+            }
+        }
+    };
+
+    if (n_tiles > 0) {
+        fetch(0);
+        stash(0);
+    }
+    __syncthreads();
+    auto step = [&](int jt, auto masked_tag) {
+        const int buf = jt & 1;
+        const bool more = jt + 1 < n_tiles;
+        if (more) fetch(jt + 1);
+        tile(buf, masked_tag);
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+    };
+    int jt = 0;
+    for (; jt < n_free; ++jt) step(jt, std::false_type{});
+    for (; jt < n_tiles; ++jt) step(jt, std::true_type{});
+
+    if (qvalid) {
+        const float sq = tau * inv_scale[s];
+        float* dqp = dq + (seg + qpos) * D + 4 * h;
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g)
+                *reinterpret_cast<float4*>(dqp + db * 32 + 8 * g) =
+                    make_float4(dqacc[db][4 * g] * sq, dqacc[db][4 * g + 1] * sq, dqacc[db][4 * g + 2] * sq, dqacc[db][4 * g + 3] * sq);
+    }
+}
+
+template <int D>
+static int launch_dq_t(const void* q, const void* k, const void* v, const void* do_perm,
+                       const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                       const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S, int T,
+                       float tau, float* dq, hipStream_t st)
+{
+    const size_t smem = sizeof(DqSmem<D>);
+    static bool attr_set = false;
+    if (!attr_set) {
+        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_f16_kernel<D>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        attr_set = true;
+    }
+    dim3 grid((unsigned)((size_t)S * n_work)), block(256);
+    hipLaunchKernelGGL(attn_bwd_dq_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
+                       (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx,
+                       work, n_work, S, T, tau, dq);
+    SCFA_HIP_TRY(hipGetLastError());
+    return SCFA_OK;
+}
+
+int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
+                            const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                            const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,
+                            int S, int T, int d, float tau, float* dq, hipStream_t st)
+{
+    ProfScope prof(SCFA_K_BWD_DQ, st);
+    if (d == 64)
+        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, dq, st);
+    if (d == 128)
+        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, dq, st);
+    return SCFA_EUNSUPPORTED;
+}
+
+}  // namespace scfa

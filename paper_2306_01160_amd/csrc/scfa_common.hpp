@@ -69,14 +69,14 @@ int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int3
                          float tau, void* o, float* lse, float* o_f32, hipStream_t st);
 int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
-                         hipStream_t st);
+                         uint32_t* amax, float* inv_scale, hipStream_t st);
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
-                              const float* lse_perm, const float* delta_perm, const int32_t* q_idx,
-                              const int32_t* k_idx, const int32_t* bwd_work, int n_bwd, int S, int T,
-                              int d, float tau, float* dk, float* dv, hipStream_t st);
+                              const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                              const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
+                              int S, int T, int d, float tau, float* dk, float* dv, hipStream_t st);
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
-                            const float* lse_perm, const float* delta_perm, const int32_t* q_idx,
-                            const int32_t* k_idx, const int32_t* fwd_work, int n_fwd, int S, int T,
-                            int d, float tau, float* dq, hipStream_t st);
+                            const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                            const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,
+                            int S, int T, int d, float tau, float* dq, hipStream_t st);
 
 }  // namespace scfa

@@ -47,10 +47,10 @@ __device__ __forceinline__ uint32_t pack_f16(float lo, float hi)
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// log2(1 + 2^-12): added to the exponent of every probability that is then truncated to
-// fp16 (11 significant bits), so that the truncation error is centred on zero instead of
-// biasing row sums and outputs low by 2^-12.
-constexpr float RTZ_BIAS_LOG2 = 3.5218e-4f;
+// Added to the exponent of every probability that is then truncated to
+// fp16: truncation loses half an ulp on average, a relative 2^-11 * E[1/mantissa] = 3.5e-4 for
+// log-uniform mantissas; scaling by 1 + 3.5e-4 first (log2 = 5.08e-4) centres the error on zero.
+constexpr float RTZ_BIAS_LOG2 = 5.08e-4f;
 
 // makes the compiler treat v as consumed here (pending loads into it are waited for)
 template <typename V>
@@ -144,9 +144,46 @@ __device__ __forceinline__ int buffer_load4(rsrc_t r, int voffset, int soffset)
     return __builtin_amdgcn_raw_buffer_load_b32(r, voffset, soffset, 0);
 }
 
+// ---------------------------------------------------------------------------
+// Swizzled tiles: row stride D (no padding); the 16-byte chunk c of row r lives at chunk
+// position c ^ swz(r).  With swz(r) = 2*(r%4) + (r/4)%2 both access patterns are free of
+// bank conflicts: 8 consecutive rows reading the same chunk (16-byte row reads) hit 8
+// different positions, and 4 consecutive rows reading the same 32-byte unit (transposing
+// reads) hit 4 different units.
+__device__ __forceinline__ int swz(int row) { return ((row & 3) << 1) | ((row >> 2) & 1); }
+
+template <int D>
+__device__ __forceinline__ int swz_offset(int row, int col)   // element offset of (row, col) in a tile
+{
+    return row * D + ((((col >> 3) ^ swz(row)) << 3) | (col & 7));
+}
+
+template <int D>
+__device__ __forceinline__ f16x8 swz_rows(const uint16_t* tile, int row, int col)
+{
+    return as_f16x8(*reinterpret_cast<const uint4*>(tile + swz_offset<D>(row, col)));
+}
+
+// element offsets of the two transposing reads of lane `lane` for the operand
+// transpose(tile[r0 .. r0+16)[c0 .. c0+32)) (see lds_trans); loop-invariant per lane
+template <int D>
+__device__ __forceinline__ void swz_trans_offsets(int r0, int c0, int lane, int& off_a, int& off_b)
+{
+    const int r = lane & 15, blk = (lane >> 4) & 1, h = lane >> 5;
+    const int row = r0 + 4 * h + (r >> 2), col = c0 + 16 * blk + 4 * (r & 3);
+    off_a = swz_offset<D>(row, col);
+    off_b = swz_offset<D>(row + 8, col);
+}
+
+__device__ __forceinline__ f16x8 swz_trans(const uint16_t* tile, int off_a, int off_b)
+{
+    const uint2 a = lds_tr_read(tile + off_a);
+    const uint2 b = lds_tr_read(tile + off_b);
+    return as_f16x8(make_uint4(a.x, a.y, b.x, b.y));
+}
+
 // Cooperative copy of ROWS contiguous rows x D fp16 (one tile) from global memory into
-// registers and on into an LDS tile with row stride STRIDE.  Rows past the end of the
-// resource read as zeros.
+// registers and on into an LDS tile.  Rows past the end of the resource read as zeros.
 template <int D, int ROWS, int THREADS>
 struct TileRegs {
     static constexpr int CHUNKS = D / 8;                   // 16-byte chunks per row
@@ -162,6 +199,7 @@ struct TileRegs {
         for (int u = 0; u < ITEMS; ++u)
             r[u] = buffer_load16(rsrc, (int)threadIdx.x * 16, tile_byte_offset + u * THREADS * 16);
     }
+    // padded layout, row stride STRIDE
     template <int STRIDE>
     __device__ __forceinline__ void store(uint16_t* tile) const
     {
@@ -170,6 +208,16 @@ struct TileRegs {
             const int item = threadIdx.x + THREADS * u;
             const int row = item / CHUNKS, c8 = item % CHUNKS;
             *reinterpret_cast<uint4*>(tile + row * STRIDE + c8 * 8) = r[u];
+        }
+    }
+    // swizzled layout, row stride D
+    __device__ __forceinline__ void store_swz(uint16_t* tile) const
+    {
+#pragma unroll
+        for (int u = 0; u < ITEMS; ++u) {
+            const int item = threadIdx.x + THREADS * u;
+            const int row = item / CHUNKS, c8 = item % CHUNKS;
+            *reinterpret_cast<uint4*>(tile + swz_offset<D>(row, c8 * 8)) = r[u];
         }
     }
 };

@@ -66,8 +66,6 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
                                                         want_bwd=need_bwd)
     o_f32 = _o_f32_buffer(q, need_bwd)
     o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f32_out=o_f32)
-    if need_bwd and f16:   # TEMP: the backward kernels still read bf16 copies
-        q_p, k_p, v_p = (sc.scfa_gather_rows(_seg(x), i) for x, i in ((q, q_idx), (k, k_idx), (v, k_idx)))
     ctx = Context(sc.SCFA_HASH, B, H, nb, sm_scale, q_p, k_p, v_p, q_idx, k_idx, None, None, fwd_work, bwd_work,
                   counters, o, lse, o_f32, q_bs, k_bs, q_off, k_off)
     return o, lse, ctx
@@ -93,8 +91,6 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True):
                                                         want_bwd=need_bwd)
     o_f32 = _o_f32_buffer(q, need_bwd)
     o, lse = sc.scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_f32_out=o_f32)
-    if need_bwd and f16:   # TEMP: the backward kernels still read bf16 copies
-        q_c, k_c, v_c = (sc.scfa_gather_rows(_seg(x), i, n) for x, i, n in ((q, q_idx, n_q), (k, k_idx, n_k), (v, k_idx, n_k)))
     ctx = Context(sc.SCFA_QKDROP, B, H, 1, sm_scale, q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work,
                   counters, o, lse, o_f32)
     return o, lse, ctx
