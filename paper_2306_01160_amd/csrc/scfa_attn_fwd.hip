@@ -24,8 +24,6 @@
 #include "scfa_mma.hpp"
 
 #include <math.h>
-#include <stdlib.h>
-
 #include <type_traits>
 
 namespace scfa {
@@ -285,11 +283,7 @@ int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int3
                          float tau, void* o, float* lse, float* o_f32, hipStream_t st)
 {
     ProfScope prof(SCFA_K_FWD, st);
-    if (d == 64) {
-        static const int variant = getenv("SCFA_FWD_VARIANT") ? atoi(getenv("SCFA_FWD_VARIANT")) : 1;
-        if (variant == 1) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
-        return launch_fwd_t<64, 2, 2>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
-    }
+    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
     if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
     return SCFA_EUNSUPPORTED;
 }

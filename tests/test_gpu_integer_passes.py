@@ -90,6 +90,22 @@ def test_gather_rows_bit_exact(dtype, d):
         assert torch.equal(out2[s, cnt[s]:], sentinel[s, cnt[s]:])
 
 
+def test_gather_rows_bf16_to_f16_compute_format():
+    """bf16 -> fp16 on the way (round to nearest even): equals torch's conversion bit for bit,
+    including values below the fp16 normal range and above its maximum (saturated)."""
+    S, T, d = 2, 777, 64
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal((S, T, d)).astype(np.float32)
+    x[0, :5] *= 1e-6          # fp16 denormals / flush
+    x[1, :3] *= 1e6           # beyond 65504: saturates
+    xb = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
+    idx = np.stack([rng.permutation(T) for _ in range(S)]).astype(np.int32)
+    out = sc.scfa_gather_rows(xb, _t(idx), to_f16=True)
+    assert out.dtype == torch.float16
+    ref = torch.gather(xb, 1, _t(idx).long()[..., None].expand(-1, -1, d)).float().clamp(-65504.0, 65504.0).to(torch.float16)
+    assert torch.equal(out, ref)
+
+
 # ------------------------------------------------------------------ schedule
 
 def _check_schedule(variant, lab_q, lab_k, nb, tiles):
