@@ -35,6 +35,21 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA peak (published)
 
 
+def measured_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a copy of known size); None if no summary covers it."""
+    path = os.path.join(ROOT, "profiles", "scfa_hot_path_config4_hash_T16384.md")
+    names = {"bwd_dkdv": "attn_bwd_dkdv_f16_kernel", "bwd_dq": "attn_bwd_dq_f16_kernel", "fwd": "attn_fwd_f16_kernel"}
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 3 and parts[0] == "hbm_traffic_bytes_per_launch" and parts[1] == names.get(kernel):
+                return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -177,7 +192,8 @@ def main():
                                f"(benchmark configuration {'4' if args.workload == 'c4' else '3'})",
                    "tiles": {"fwd": [fm, fn], "bwd": [bm, bn]}},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS, "traffic": None,
+                     "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
+                     "traffic": measured_traffic(dominant) if args.workload == "c4" else None,
                      "avg_launch_ms": kt[dominant]["avg_ms"]},
         "computed_tile_tflops_kernels": computed_tile_flops / (attn_ms * 1e-3) / 1e12,
         "computed_tile_frac_of_mfma_peak": computed_tile_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,

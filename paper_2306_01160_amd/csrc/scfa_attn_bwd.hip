@@ -49,7 +49,13 @@ __global__ __launch_bounds__(256) void dout_amax_kernel(const uint4* __restrict_
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
-    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(&amax[s], m);
+    __shared__ uint32_t wave_max[4];
+    if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {   // one atomic per workgroup: the [S] targets are heavily shared
+        m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
+        if (m != 0) atomicMax(&amax[s], m);
+    }
 }
 
 // power-of-two scale that brings a magnitude with these float bits into [1, 2)
@@ -130,7 +136,7 @@ int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, co
     hipLaunchKernelGGL(fill_u32_kernel, dim3((S + 255) / 256), dim3(256), 0, st, amax, S, 0u);
     const long long chunks = (long long)T * d / 8;
     const long long want = (chunks + 256 * 8 - 1) / (256 * 8);
-    const unsigned nblk = (unsigned)(want < 256 ? want : 256);
+    const unsigned nblk = (unsigned)(want < 64 ? want : 64);
     hipLaunchKernelGGL(dout_amax_kernel, dim3(nblk, S), dim3(256), 0, st, (const uint4*)d_o, chunks, amax);
     const long long threads = (long long)T * (d / 8);
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
