@@ -102,13 +102,21 @@ int scfa_compact_keep(const uint8_t *keep, int S, int T,
  * compacted Q, K, V the kernels consume).  x and out must be 16-byte aligned
  * and must not overlap.  dtype: SCFA_BF16 or SCFA_F32; d*sizeof(elem) must be a
  * multiple of 16.
- * out_dtype: equal to dtype (bit-exact copy), or SCFA_F16 for SCFA_BF16 input: the
- * compute format of the attention kernels.  bf16 -> fp16 rounds to nearest even; it is
- * exact for magnitudes in [2^-17, 65504], smaller ones lose low bits (absolute error
- * < 2^-25), larger ones saturate at 65504.
+ * out_dtype: equal to dtype, or SCFA_F16 for SCFA_BF16 input: the compute format of
+ * the attention kernels.  bf16 -> fp16 rounds to nearest even; it is exact for
+ * magnitudes in [2^-17, 65504], smaller ones lose low bits (absolute error < 2^-25),
+ * larger ones saturate at 65504.
+ * scale: every element is multiplied by `scale` before the single rounding to
+ * out_dtype.  scale == 1 with out_dtype == dtype is a bit-exact copy; bf16 -> bf16
+ * with another scale is SCFA_EUNSUPPORTED.  The attention entry points expect the
+ * QUERIES gathered with scale = scfa_q_scale(sm_scale) = sm_scale * log2(e) (their
+ * score contraction then yields base-2 exponents directly, see b.); keys, values
+ * and everything else are gathered with scale 1.
  */
+float scfa_q_scale(float sm_scale);
 int scfa_gather_rows(const void *x, const int32_t *idx, const int32_t *count,
-                     int S, int T, int d, int dtype, int out_dtype, void *out, void *stream);
+                     int S, int T, int d, int dtype, int out_dtype, float scale,
+                     void *out, void *stream);
 
 /* ------------------------------------------------------------------------
  * a4. Tile-skip schedule.  The paper finds, per block of queries, the range of
@@ -168,10 +176,15 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  *
  *   q_perm,k_perm,v_perm  [S,T,d] rows in sorted (hash) or compacted (qkdrop) order, as
  *                         scfa_gather_rows writes them: fp32 for SCFA_F32, fp16
- *                         (out_dtype = SCFA_F16) for SCFA_BF16
+ *                         (out_dtype = SCFA_F16) for SCFA_BF16.  q_perm must have been
+ *                         gathered with scale = scfa_q_scale(sm_scale): the kernels
+ *                         take <q_perm, k_perm> as the exponent in base 2 and apply no
+ *                         scaling of their own (one rounding of q * tau * log2 e to the
+ *                         compute format: relative 2^-12 per element for fp16)
  *   q_idx,k_idx           [S,T] original positions of those rows
  *   fwd_work, n_fwd       work list of scfa_block_ranges
- *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d))
+ *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d)); the same value
+ *                         the queries were gathered with
  *   o_out                 [B,H,T,d] in ORIGINAL order, dtype of the inputs
  *   lse_out               [B,H,T] float, ORIGINAL order: natural-log logsumexp of the
  *                         scaled scores over allowed keys; -inf for a row with none
@@ -212,7 +225,10 @@ int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
  *                 (dK, dV) are written as zeros
  *   ws, ws_bytes  scratch of at least scfa_attn_bwd_workspace_bytes(S,T,d,dtype),
  *                 256-byte aligned; contents are undefined afterwards
- * dtype: SCFA_BF16 only.
+ * q_perm carries tau * log2(e) as in the forward.  dtype: SCFA_BF16 only.  Per query the
+ * kernels hold LSE * log2(e) and D * (power-of-two dO scale) as sums of three fp16
+ * numbers; magnitudes above 60000 are clamped there (|D| <= 2 d max|O| after the
+ * scaling of dO, so this needs |O| in the thousands).
  *
  * scfa_qkdrop_attn_bwd additionally takes n_q, n_k [S] (kept counts).
  */

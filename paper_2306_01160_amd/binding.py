@@ -26,7 +26,7 @@ KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_
 
 EXPORTS = [
     "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket",
-    "scfa_compact_keep", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
+    "scfa_compact_keep", "scfa_q_scale", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
     "scfa_attn_bwd_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
     "scfa_prof_enable", "scfa_prof_reset", "scfa_prof_read",
@@ -53,7 +53,9 @@ def lib():
         L.scfa_error_string.argtypes = [ci]
         L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp]
-        L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, vp]
+        L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp]
+        L.scfa_q_scale.argtypes = [ctypes.c_float]
+        L.scfa_q_scale.restype = ctypes.c_float
         L.scfa_block_ranges.argtypes = [ci, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_num_work_items.argtypes = [ci, ci, ci]
         ip = ctypes.POINTER(ci)
@@ -70,7 +72,7 @@ def lib():
         L.scfa_prof_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ip]
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes"):
+            if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes", "scfa_q_scale"):
                 fn.restype = ci
         _lib = L
     return _lib
@@ -145,15 +147,20 @@ def scfa_compact_keep(keep: torch.Tensor):
     return idx, count
 
 
-def scfa_gather_rows(x: torch.Tensor, idx: torch.Tensor, count=None, out=None, to_f16=False):
-    """x [S,T,d], idx [S,T] -> out [S,T,d] with out[s,r] = x[s, idx[s,r]] for r < count[s] (or T).
+def scfa_q_scale(tau: float) -> float:
+    """The factor the attention kernels expect on the gathered queries: tau * log2(e)."""
+    return float(lib().scfa_q_scale(float(tau)))
+
+
+def scfa_gather_rows(x: torch.Tensor, idx: torch.Tensor, count=None, out=None, to_f16=False, scale=1.0):
+    """x [S,T,d], idx [S,T] -> out [S,T,d] with out[s,r] = scale * x[s, idx[s,r]] for r < count[s] (or T).
     to_f16: bf16 input is written in the fp16 compute format of the attention kernels."""
     S, T, d = x.shape
     if out is None:
         out = torch.empty(x.shape, dtype=torch.float16 if to_f16 else x.dtype, device=x.device)
     out_code = SCFA_F16 if to_f16 else dtype_code(x)
-    _check(lib().scfa_gather_rows(_ptr(x), _ptr(idx), _ptr(count), S, T, d, dtype_code(x), out_code, _ptr(out),
-                                  _stream()), "scfa_gather_rows")
+    _check(lib().scfa_gather_rows(_ptr(x), _ptr(idx), _ptr(count), S, T, d, dtype_code(x), out_code, float(scale),
+                                  _ptr(out), _stream()), "scfa_gather_rows")
     return out
 
 

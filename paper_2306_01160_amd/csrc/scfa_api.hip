@@ -118,6 +118,8 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
     w += align_up((size_t)S * T * 4, 256);
     float* lse_perm = reinterpret_cast<float*>(w);
     w += align_up((size_t)S * T * 4, 256);
+    void* aux_perm = w;                         // [S,T,8] fp16: pieces of LSE log2 e and D
+    w += align_up((size_t)S * T * 16, 256);
     uint32_t* amax = reinterpret_cast<uint32_t*>(w);
     w += align_up((size_t)S * 4, 256);
     float* inv_scale = reinterpret_cast<float*>(w);
@@ -128,10 +130,10 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
         rc = launch_zero_rows(k_idx, n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
     }
-    rc = launch_bwd_prep_bf16(o, o_f32, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, amax, inv_scale, st);
+    rc = launch_bwd_prep_bf16(o, o_f32, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
-    rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd,
-                                   S, T, d, sm_scale, dk, dv, st);
+    rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, d,
+                                   dk, dv, st);
     if (rc != SCFA_OK) return rc;
     return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd,
                                    S, T, d, sm_scale, dq, st);
@@ -173,16 +175,20 @@ int scfa_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32
     return launch_compact_keep(keep, S, T, idx_out, count_out, (hipStream_t)stream);
 }
 
+float scfa_q_scale(float tau) { return tau * 1.4426950408889634f; }
+
 int scfa_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T, int d, int dtype,
-                     int out_dtype, void* out, void* stream)
+                     int out_dtype, float scale, void* out, void* stream)
 {
-    if (!x || !idx || !out || S <= 0 || T <= 0 || d <= 0) return SCFA_EINVAL;
+    if (!x || !idx || !out || S <= 0 || T <= 0 || d <= 0 || !(scale == scale)) return SCFA_EINVAL;
     if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
     if (out_dtype != dtype && !(dtype == SCFA_BF16 && out_dtype == SCFA_F16)) return SCFA_EUNSUPPORTED;
+    if (scale != 1.0f && dtype == SCFA_BF16 && out_dtype == SCFA_BF16) return SCFA_EUNSUPPORTED;   // bf16 copies are bit-exact only
+    const int mode = out_dtype != dtype ? 1 : (scale != 1.0f ? 2 : 0);
     const long long row_bytes = (long long)d * (dtype == SCFA_BF16 ? 2 : 4);
     if (row_bytes % 16 != 0 || !aligned16(x) || !aligned16(out)) return SCFA_EINVAL;
     if (S > 65535 || (long long)T * (row_bytes / 16) / 256 > 0x7fffffffLL) return SCFA_EUNSUPPORTED;
-    return launch_gather_rows(x, idx, count, S, T, (int)row_bytes, out_dtype != dtype, out, (hipStream_t)stream);
+    return launch_gather_rows(x, idx, count, S, T, (int)row_bytes, mode, scale, out, (hipStream_t)stream);
 }
 
 int scfa_num_work_items(int T, int nb, int tile)
@@ -249,7 +255,7 @@ size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype)
 {
     if (S <= 0 || T <= 0 || d <= 0 || dtype != SCFA_BF16) return 0;
     return align_up((size_t)S * T * d * 2, 256) + 2 * align_up((size_t)S * T * 4, 256) +
-           2 * align_up((size_t)S * 4, 256);
+           align_up((size_t)S * T * 16, 256) + 2 * align_up((size_t)S * 4, 256);
 }
 
 int scfa_hash_attn_bwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,

@@ -13,6 +13,18 @@
 // dO is multiplied by a power of two per (batch, head) segment so that its largest
 // magnitude lies in [1, 2) before it is converted to fp16; the gradients are multiplied
 // by the inverse power at the end.  Both scalings are exact.
+//
+// The permuted queries arrive multiplied by tau * log2(e) (the forward's convention), so
+// Q K^T is the score in base-2 units and dK = ln 2 * dS^T Q'.  The per-row subtractions of
+// P = 2^(x - LSE log2 e) and dS = P (dP - D) are folded into the contractions:
+//   - where the row is a lane (dQ kernel) the accumulators start from -LSE log2 e and -D;
+//   - where the row is a register (dK/dV kernel) one more contraction step of 16 slots is
+//     appended: the pre-pass writes, per query, LSE log2 e and D split into three fp16
+//     pieces each (an 8-element "aux" row, pieces 2 and 3 scaled by 2^11), and the key side
+//     of that step is the constant (-1, -2^-11, -2^-11, 0 | 0, 0, 0, 0) for the score
+//     and (0, 0, 0, 0 | -1, -2^-11, -2^-11, 0) for dP.  Products of fp16 numbers are exact
+//     in the fp32 accumulation, so the split only costs the final fp32 rounding.
+// What is left per element is one exponential, one product and the fp16 packing.
 #include "scfa_common.hpp"
 #include "scfa_mma.hpp"
 
@@ -68,13 +80,29 @@ __device__ __forceinline__ void pow2_scales(uint32_t amax_bits, float& scale, fl
     inv_scale = __uint_as_float((uint32_t)e << 23);          // 2^(e-127)
 }
 
+// x (clamped to +-AUX_LIMIT) = h1 + 2^-11 h2 + 2^-11 h3 with fp16 h1, h2, h3, to about 33 bits;
+// packed as (h1, h2), (h3, 0).  Every piece stays in the normal fp16 range or is negligible.
+constexpr float AUX_LIMIT = 60000.f;
+constexpr float AUX_PIECE = 2048.f;   // 2^11
+__device__ __forceinline__ void split3(float x, uint32_t& w01, uint32_t& w23)
+{
+    x = fminf(fmaxf(x, -AUX_LIMIT), AUX_LIMIT);
+    const _Float16 h1 = (_Float16)x;
+    const float r1 = x - (float)h1;                       // exact
+    const _Float16 h2 = (_Float16)(r1 * AUX_PIECE);
+    const float r2 = r1 - (float)h2 * (1.f / AUX_PIECE);  // exact
+    const _Float16 h3 = (_Float16)(r2 * AUX_PIECE);
+    w01 = (uint32_t)__builtin_bit_cast(uint16_t, h1) | ((uint32_t)__builtin_bit_cast(uint16_t, h2) << 16);
+    w23 = (uint32_t)__builtin_bit_cast(uint16_t, h3);
+}
+
 // One row is handled by D/8 adjacent lanes (16 bytes of dO each).
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const uint16_t* __restrict__ o, const float* __restrict__ o_f32, const float* __restrict__ lse,
     const uint16_t* __restrict__ d_o, const int32_t* __restrict__ q_idx, const uint32_t* __restrict__ amax,
     int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
-    float* __restrict__ inv_scale_out)
+    uint16_t* __restrict__ aux_perm, float* __restrict__ inv_scale_out)
 {
     constexpr int LPR = D / 8;   // lanes per row
     const int s = blockIdx.y;
@@ -123,14 +151,21 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
 #pragma unroll
     for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (valid && c8 == 0) {
+        const float lse_r = lse[seg + src];
         delta_perm[seg + r] = acc;
-        lse_perm[seg + r] = lse[seg + src];
+        lse_perm[seg + r] = lse_r;
+        // a row without keys gets an exponent offset that makes every probability 0
+        const float l2 = lse_r != -INFINITY ? fmaf(lse_r, LOG2E, -RTZ_BIAS_LOG2) : AUX_LIMIT;
+        uint32_t w[4];
+        split3(l2, w[0], w[1]);
+        split3(acc, w[2], w[3]);
+        *reinterpret_cast<uint4*>(aux_perm + (seg + r) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
 int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
-                         uint32_t* amax, float* inv_scale, hipStream_t st)
+                         void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_PREP, st);
     hipLaunchKernelGGL(fill_u32_kernel, dim3((S + 255) / 256), dim3(256), 0, st, amax, S, 0u);
@@ -142,10 +177,10 @@ int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, co
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
     if (d == 64)
         hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
-                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, inv_scale);
+                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else if (d == 128)
         hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
-                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, inv_scale);
+                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());
@@ -155,8 +190,9 @@ int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, co
 // ===========================================================================
 // dK / dV: a workgroup owns 128 keys of one bucket (32 per wavefront, in the lanes)
 // and walks the 64-row query tiles that can see them.  Per tile:
-//   S = Q K^T, dP = dO V^T (queries x keys; lane = key, registers = queries)
-//   P = exp2(c S - LSE log2 e), dS = P (dP - D)
+//   X = Q' K^T - LSE log2 e, dP' = dO V^T - D (queries x keys; lane = key, registers =
+//   queries; the subtractions ride in a 16-slot contraction step on the aux rows)
+//   P = 2^X, dS = P dP'
 //   dV^T += dO^T P,  dK^T += Q^T dS   (d x keys; Q^T, dO^T by transposing LDS reads)
 // ===========================================================================
 template <int D>
@@ -164,18 +200,17 @@ struct DkdvSmem {
     static constexpr int BM = BWD_TILE_M;
     uint16_t Qs[2][BM * D];
     uint16_t Gs[2][BM * D];     // dO rows
-    float lse2[2][BM];          // LSE * log2(e); +inf for rows that contribute nothing
-    float delta[2][BM];
+    uint16_t aux[2][BM * 8];    // per query: three fp16 pieces of LSE log2 e and of D
     int32_t qpos[2][BM];
 };
 
 template <int D>
 __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
-    const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
+    const uint16_t* __restrict__ do_perm, const uint16_t* __restrict__ aux_perm,
+    const float* __restrict__ inv_scale,
     const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
-    const int32_t* __restrict__ work, int n_work, int S, int T, float tau,
+    const int32_t* __restrict__ work, int n_work, int S, int T,
     float* __restrict__ dk, float* __restrict__ dv)
 {
     constexpr int BM = BWD_TILE_M;
@@ -210,10 +245,20 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         for (int kk = 0; kk < D / 16; ++kk) { touch(kf[kk]); touch(vf[kk]); }
     }
 
+    // key side of the appended contraction step (lanes 32-63 hold slots 8-15: all zero)
+    f16x8 sub_lse, sub_delta;
+    {
+        const _Float16 one = h == 0 ? (_Float16)-1.f : (_Float16)0.f;
+        const _Float16 piece = h == 0 ? (_Float16)(-1.f / AUX_PIECE) : (_Float16)0.f;
+        const _Float16 z = (_Float16)0.f;
+        sub_lse = f16x8{one, piece, piece, z, z, z, z, z};
+        sub_delta = f16x8{z, z, z, z, one, piece, piece, z};
+        touch(sub_lse); touch(sub_delta);
+    }
+
     f32x16 dkacc[D / 32], dvacc[D / 32];
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) { dkacc[db] = zero16(); dvacc[db] = zero16(); }
-    const float c = tau * LOG2E;
 
     const int n_tiles = (q_count + BM - 1) / BM;
     const int n_masked = min((q_masked + BM - 1) / BM, n_tiles);   // leading tiles that need the causal test
@@ -221,28 +266,26 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     TileRegs<D, BM, 256> qt, gt;
     const rsrc_t q_rsrc = make_rsrc(q + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
     const rsrc_t g_rsrc = make_rsrc(do_perm + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
-    const rsrc_t l_rsrc = make_rsrc(lse_perm + seg + q_begin, (uint32_t)q_count * 4);
-    const rsrc_t d_rsrc = make_rsrc(delta_perm + seg + q_begin, (uint32_t)q_count * 4);
+    const rsrc_t a_rsrc = make_rsrc(aux_perm + (seg + q_begin) * 8, (uint32_t)q_count * 16);
     const rsrc_t p_rsrc = make_rsrc(q_idx + seg + q_begin, (uint32_t)q_count * 4);
-    float lse_reg = 0.f, delta_reg = 0.f;
+    uint4 aux_reg = make_uint4(0u, 0u, 0u, 0u);
     int qp_reg = 0, q_row = 0;
     auto fetch = [&](int jt) {
         qt.load(q_rsrc, jt * qt.TILE_BYTES);
         gt.load(g_rsrc, jt * gt.TILE_BYTES);
         if (tid < BM) {
-            lse_reg = __int_as_float(buffer_load4(l_rsrc, tid * 4, jt * BM * 4));
-            delta_reg = __int_as_float(buffer_load4(d_rsrc, tid * 4, jt * BM * 4));
+            aux_reg = buffer_load16(a_rsrc, tid * 16, jt * BM * 16);
             qp_reg = buffer_load4(p_rsrc, tid * 4, jt * BM * 4);
             q_row = jt * BM + tid;
         }
     };
+    // Rows past the end of the range read as zeros everywhere (Q, dO, aux): P = 1 there, but
+    // dO = 0 and dP' = 0 make their contributions to dV and dK vanish.
     auto stash = [&](int buf) {
         qt.store_swz(sm.Qs[buf]);
         gt.store_swz(sm.Gs[buf]);
         if (tid < BM) {
-            const bool ok = q_row < q_count && lse_reg != -INFINITY;   // rows past the end / without keys: P = 0
-            sm.lse2[buf][tid] = ok ? fmaf(lse_reg, LOG2E, -RTZ_BIAS_LOG2) : INFINITY;
-            sm.delta[buf][tid] = delta_reg;
+            *reinterpret_cast<uint4*>(&sm.aux[buf][tid * 8]) = aux_reg;
             sm.qpos[buf][tid] = q_row < q_count ? qp_reg : -1;
         }
     };
@@ -253,7 +296,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         const uint16_t* Gt = sm.Gs[buf];
         f32x16 sacc[2], pacc[2];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) { sacc[qb] = zero16(); pacc[qb] = zero16(); }
+        for (int qb = 0; qb < 2; ++qb) {
+            const f16x8 ax = as_f16x8(*reinterpret_cast<const uint4*>(&sm.aux[buf][(qb * 32 + l32) * 8]));
+            sacc[qb] = mfma16(ax, sub_lse, zero16());
+            pacc[qb] = mfma16(ax, sub_delta, zero16());
+        }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
@@ -266,22 +313,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int r = qb * 32 + 8 * g + 4 * h;
-                const float4 l2 = *reinterpret_cast<const float4*>(&sm.lse2[buf][r]);
-                const float4 dl = *reinterpret_cast<const float4*>(&sm.delta[buf][r]);
-                const float l2a[4] = {l2.x, l2.y, l2.z, l2.w};
-                const float dla[4] = {dl.x, dl.y, dl.z, dl.w};
                 int qpa[4] = {0, 0, 0, 0};
                 if (MASKED) {
-                    const int4 qp = *reinterpret_cast<const int4*>(&sm.qpos[buf][r]);
+                    const int4 qp = *reinterpret_cast<const int4*>(&sm.qpos[buf][qb * 32 + 8 * g + 4 * h]);
                     qpa[0] = qp.x; qpa[1] = qp.y; qpa[2] = qp.z; qpa[3] = qp.w;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(fmaf(sacc[qb][4 * g + e], c, -l2a[e]));
+                    float p = fast_exp2(sacc[qb][4 * g + e]);
                     if (MASKED) { if (kpos > qpa[e]) p = 0.f; }     // causal test on original positions
                     sacc[qb][4 * g + e] = p;
-                    pacc[qb][4 * g + e] = p * (pacc[qb][4 * g + e] - dla[e]);
+                    pacc[qb][4 * g + e] = p * pacc[qb][4 * g + e];
                 }
             }
 
@@ -318,7 +360,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 
     if (kvalid) {
         const float us = inv_scale[s];
-        const float sk = tau * us;
+        const float sk = LN2 * us;   // Q' = tau log2(e) Q: dK = tau dS^T Q = ln 2 dS^T Q'
         float* dkp = dk + (seg + kpos) * D + 4 * h;
         float* dvp = dv + (seg + kpos) * D + 4 * h;
 #pragma unroll
@@ -335,9 +377,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 
 template <int D>
 static int launch_dkdv_t(const void* q, const void* k, const void* v, const void* do_perm,
-                         const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                         const void* aux_perm, const float* inv_scale,
                          const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S,
-                         int T, float tau, float* dk, float* dv, hipStream_t st)
+                         int T, float* dk, float* dv, hipStream_t st)
 {
     const size_t smem = sizeof(DkdvSmem<D>);
     static bool attr_set = false;
@@ -348,29 +390,30 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
     }
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
-                       (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx,
-                       work, n_work, S, T, tau, dk, dv);
+                       (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_idx, k_idx,
+                       work, n_work, S, T, dk, dv);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
-                              const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                              const void* aux_perm, const float* inv_scale,
                               const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, float tau, float* dk, float* dv, hipStream_t st)
+                              int S, int T, int d, float* dk, float* dv, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DKDV, st);
     if (d == 64)
-        return launch_dkdv_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, tau, dk, dv, st);
+        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, dk, dv, st);
     if (d == 128)
-        return launch_dkdv_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, tau, dk, dv, st);
+        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, dk, dv, st);
     return SCFA_EUNSUPPORTED;
 }
 
 // ===========================================================================
 // dQ: same walk as the forward (a workgroup owns 128 queries of one bucket, 32 per
 // wavefront in the lanes; keys 64 at a time).  Per tile:
-//   S^T = K Q^T, dP^T = V dO^T (keys x queries), dS^T = P^T (dP^T - D), dQ^T += K^T dS^T
+//   X^T = K Q'^T - LSE log2 e, dP'^T = V dO^T - D (keys x queries; the accumulators start
+//   from the per-lane constants), P^T = 2^X^T, dS^T = P^T dP'^T, dQ^T += K^T dS^T
 // ===========================================================================
 template <int D>
 struct DqSmem {
@@ -423,10 +466,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         for (int kk = 0; kk < D / 16; ++kk) { touch(qf[kk]); touch(gf[kk]); }
     }
 
-    f32x16 dqacc[D / 32];
+    f32x16 dqacc[D / 32], s_start, p_start;   // loop-invariant accumulator starts: -LSE log2 e, -D
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) dqacc[db] = zero16();
-    const float c = tau * LOG2E;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s_start[i] = -lse2; p_start[i] = -delta; }
 
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = min(k_nomask / BN, n_tiles);
@@ -456,7 +500,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         const uint16_t* Vt = sm.Vs[buf];
         f32x16 sacc[2], pacc[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) { sacc[kb] = zero16(); pacc[kb] = zero16(); }
+        for (int kb = 0; kb < 2; ++kb) { sacc[kb] = s_start; pacc[kb] = p_start; }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
@@ -476,9 +520,9 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(fmaf(sacc[kb][4 * g + e], c, -lse2));
+                    float p = fast_exp2(sacc[kb][4 * g + e]);
                     if (MASKED) { if (kpa[e] > qpos) p = 0.f; }     // causal test on original positions
-                    pacc[kb][4 * g + e] = p * (pacc[kb][4 * g + e] - delta);
+                    pacc[kb][4 * g + e] = p * pacc[kb][4 * g + e];
                 }
             }
 

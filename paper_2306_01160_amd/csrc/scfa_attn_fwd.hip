@@ -12,14 +12,20 @@
 // B-operand layout of O^T += V^T P^T.  V^T comes from the row-major V tile through
 // transposing LDS reads.
 //
+// The permuted queries arrive multiplied by tau * log2(e), so the contraction yields the
+// scores in base-2 units, x = tau * log2(e) * <q, k>, and no scaling is left per element.
+//
 // Online softmax (paper App. B.1, running maximum and sum, NaN-safe for fully masked
 // rows): the accumulator is un-normalised and divided by the sum once at the end.  The
 // reference maximum m is only raised when some row's tile maximum exceeds it by more
-// than 2^LAZY_LOG2 (then the accumulator and the sum are rescaled by exp(m_old - m_new));
-// between raises P = exp(s - m) may exceed 1 but stays far inside the fp16 range.  A
-// row that never sees an allowed key keeps m = -inf and l = 0; its exponent base is 0
-// (the paper's replacement of -inf by 0), every p is exp(-inf) = 0, and it is written
-// as zeros with LSE = -inf.
+// than LAZY_LOG2 (then the accumulator and the sum are rescaled by 2^(m_old - m_new));
+// between raises P = 2^(x - m) may exceed 1 but stays far inside the fp16 range.  Because
+// m changes rarely, -m is kept splatted over an accumulator block and the score
+// contraction starts from it: the matrix core delivers x - m and the only per-element
+// vector work left is the exponential, the packing and the row sum.  A row that never
+// sees an allowed key keeps m = -inf and l = 0; its exponent base is 0 (the paper's
+// replacement of -inf by 0), every p is 2^(-inf) = 0, and it is written as zeros with
+// LSE = -inf.
 #include "scfa_common.hpp"
 #include "scfa_mma.hpp"
 
@@ -38,6 +44,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     uint16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ o_f32)
 {
     static_assert(NW * QB * 32 == FWD_TILE_M, "workgroup must cover the forward query tile");
+    (void)tau;   // already folded into the permuted queries
     constexpr int BN = FWD_TILE_N;
     constexpr int THREADS = NW * 64;
     constexpr int KST = D + 8;    // K tile row stride: 16-byte row reads conflict-free
@@ -80,15 +87,16 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         for (int kk = 0; kk < D / 16; ++kk) touch(qf[b][kk]);   // loaded before the tile loop starts
 
     f32x16 oacc[QB][D / 32];
-    float m[QB], mc[QB], lsum[QB];   // reference max (raw score units), m*c with -inf -> 0, partial row sum
+    f32x16 start[QB];                // RTZ_BIAS_LOG2 - (finite reference maximum), in all 16 registers
+    float m[QB], thr[QB], lsum[QB];  // reference maximum (base-2 units), raise threshold on x - m, partial row sum
 #pragma unroll
     for (int b = 0; b < QB; ++b) {
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) oacc[b][db] = zero16();
-        m[b] = -INFINITY; mc[b] = -RTZ_BIAS_LOG2; lsum[b] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) start[b][i] = RTZ_BIAS_LOG2;
+        m[b] = -INFINITY; thr[b] = -INFINITY; lsum[b] = 0.f;   // the first finite score always raises
     }
-    const float c = tau * LOG2E;
-    const float lazy = LAZY_LOG2 / c;
 
     const uint16_t* kbase = k + (seg + k_begin) * D;
     const uint16_t* vbase = v + (seg + k_begin) * D;
@@ -119,12 +127,12 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         constexpr bool MASKED = decltype(masked_tag)::value;
         const uint16_t* Kt = Ks[buf];
         const uint16_t* Vt = Vs[buf];
-        // S^T = K Q^T : [key block kb][query block b]
+        // S^T = K Q^T - m : [key block kb][query block b]
         f32x16 sacc[2][QB];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int b = 0; b < QB; ++b) sacc[kb][b] = zero16();
+            for (int b = 0; b < QB; ++b) sacc[kb][b] = start[b];
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
@@ -162,26 +170,35 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                 a1 = fmaxf(a1, fmaxf(sacc[1][b][i], sacc[1][b][(i + 1) & 15]));
             }
             mx[b] = fmaxf(a0, a1);
-            raise |= mx[b] > m[b] + lazy;               // -inf > -inf is false: no NaN is ever formed
+            raise |= mx[b] > thr[b];                    // -inf > -inf is false: no NaN is ever formed
         }
         if (__ballot(raise) != 0ull) {
 #pragma unroll
             for (int b = 0; b < QB; ++b) {
-                const float m_new = fmaxf(m[b], half_max(mx[b]));
+                const float st_old = start[b][0];
+                const float m_new = fmaxf(m[b], half_max(mx[b]) - st_old);   // tile maximum back in score units
                 const float m_use = m_new == -INFINITY ? 0.f : m_new;
-                float alpha = fast_exp2((m[b] - m_use) * c);           // m = -inf -> 0
+                float alpha = fast_exp2(m[b] - m_use);                       // m = -inf -> 0
                 asm volatile("" : "+v"(alpha));   // rare path: keeps the rescale from being speculated
                 lsum[b] *= alpha;
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) oacc[b][db][i] *= alpha;
+                const float st_new = RTZ_BIAS_LOG2 - m_use;
+                const float shift = st_new - st_old;    // scores of this tile move to the new reference
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[kb][b][i] += shift;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) start[b][i] = st_new;
                 m[b] = m_new;
-                mc[b] = m_use * c - RTZ_BIAS_LOG2;
+                thr[b] = m_new == -INFINITY ? -INFINITY : LAZY_LOG2;
             }
         }
 
-        // P = exp2(c s - c m), packed to fp16; row sums from the packed values
+        // P = 2^(x - m), packed to fp16; row sums from the packed values
         f16x8 pf[QB][4];
 #pragma unroll
         for (int b = 0; b < QB; ++b) {
@@ -193,8 +210,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                     uint32_t wv[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float p0 = fast_exp2(fmaf(sacc[kb][b][8 * cc + 2 * j], c, -mc[b]));
-                        const float p1 = fast_exp2(fmaf(sacc[kb][b][8 * cc + 2 * j + 1], c, -mc[b]));
+                        const float p0 = fast_exp2(sacc[kb][b][8 * cc + 2 * j]);
+                        const float p1 = fast_exp2(sacc[kb][b][8 * cc + 2 * j + 1]);
                         wv[j] = pack_f16(p0, p1);
                     }
                     l0 = add_pair(wv[0], l0); l1 = add_pair(wv[1], l1);
@@ -253,7 +270,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                     *reinterpret_cast<uint2*>(o + row + db * 32 + 8 * g) = pk;
                     if (o_f32) *reinterpret_cast<float4*>(o_f32 + row + db * 32 + 8 * g) = make_float4(x0, x1, x2, x3);
                 }
-            if (h == 0) lse[seg + qpos[b]] = ltot > 0.f ? fmaf(m[b], tau, logf(ltot)) : -INFINITY;
+            if (h == 0) lse[seg + qpos[b]] = ltot > 0.f ? (m[b] + log2f(ltot)) * LN2 : -INFINITY;
         }
     }
 }

@@ -54,7 +54,7 @@ int launch_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* 
 int launch_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out,
                         hipStream_t st);
 int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
-                       int row_bytes, bool bf16_to_f16, void* out, hipStream_t st);
+                       int row_bytes, int mode, float scale, void* out, hipStream_t st);
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
                         int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
@@ -69,11 +69,11 @@ int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int3
                          float tau, void* o, float* lse, float* o_f32, hipStream_t st);
 int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
-                         uint32_t* amax, float* inv_scale, hipStream_t st);
+                         void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st);
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
-                              const float* lse_perm, const float* delta_perm, const float* inv_scale,
+                              const void* aux_perm, const float* inv_scale,
                               const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, float tau, float* dk, float* dv, hipStream_t st);
+                              int S, int T, int d, float* dk, float* dv, hipStream_t st);
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
                             const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,

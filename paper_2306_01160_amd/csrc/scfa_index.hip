@@ -152,12 +152,14 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restric
     out[((size_t)s * T + r) * chunks_per_row + c] = x[((size_t)s * T + src) * chunks_per_row + c];
 }
 
-// Same gather for bf16 rows, converting to fp16 on the way (round to nearest even; exact
-// for magnitudes in [2^-17, 65504], larger ones saturate to the largest fp16).
+// Same gather for bf16 rows, multiplying by `scale` and converting to fp16 on the way (one
+// rounding to nearest even; with scale 1 exact for magnitudes in [2^-17, 65504]; larger
+// results saturate to the largest fp16).
 __global__ __launch_bounds__(256) void gather_rows_bf16_to_f16_kernel(const uint4* __restrict__ x,
                                                                       const int32_t* __restrict__ idx,
                                                                       const int32_t* __restrict__ count, int T,
-                                                                      int chunks_per_row, uint4* __restrict__ out)
+                                                                      int chunks_per_row, float scale,
+                                                                      uint4* __restrict__ out)
 {
     const int s = blockIdx.y;
     const int n = count ? count[s] : T;
@@ -171,7 +173,7 @@ __global__ __launch_bounds__(256) void gather_rows_bf16_to_f16_kernel(const uint
     uint32_t o[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        float lo = __uint_as_float(w[i] << 16), hi = __uint_as_float(w[i] & 0xffff0000u);
+        float lo = __uint_as_float(w[i] << 16) * scale, hi = __uint_as_float(w[i] & 0xffff0000u) * scale;
         lo = fminf(fmaxf(lo, -65504.f), 65504.f);
         hi = fminf(fmaxf(hi, -65504.f), 65504.f);
         const _Float16 a = (_Float16)lo, b = (_Float16)hi;
@@ -180,16 +182,39 @@ __global__ __launch_bounds__(256) void gather_rows_bf16_to_f16_kernel(const uint
     out[((size_t)s * T + r) * chunks_per_row + c] = make_uint4(o[0], o[1], o[2], o[3]);
 }
 
-int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
-                       int row_bytes, bool bf16_to_f16, void* out, hipStream_t st)
+// fp32 rows multiplied by `scale` (one rounding)
+__global__ __launch_bounds__(256) void gather_rows_f32_scaled_kernel(const float4* __restrict__ x,
+                                                                     const int32_t* __restrict__ idx,
+                                                                     const int32_t* __restrict__ count, int T,
+                                                                     int chunks_per_row, float scale,
+                                                                     float4* __restrict__ out)
 {
-    if (bf16_to_f16) {
+    const int s = blockIdx.y;
+    const int n = count ? count[s] : T;
+    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
+    const int r = (int)(g / chunks_per_row);
+    const int c = (int)(g % chunks_per_row);
+    if (r >= n) return;
+    const int src = idx[(size_t)s * T + r];
+    const float4 v = x[((size_t)s * T + src) * chunks_per_row + c];
+    out[((size_t)s * T + r) * chunks_per_row + c] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
+}
+
+// mode: 0 = bit-exact copy, 1 = bf16 -> scaled fp16, 2 = scaled fp32
+int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
+                       int row_bytes, int mode, float scale, void* out, hipStream_t st)
+{
+    if (mode != 0) {
         const int cpr = row_bytes / 16;
         const long long total = (long long)T * cpr;
         dim3 grid((unsigned)((total + 255) / 256), S);
         ProfScope prof(SCFA_K_GATHER, st);
-        hipLaunchKernelGGL(gather_rows_bf16_to_f16_kernel, grid, dim3(256), 0, st, (const uint4*)x, idx, count, T,
-                           cpr, (uint4*)out);
+        if (mode == 1)
+            hipLaunchKernelGGL(gather_rows_bf16_to_f16_kernel, grid, dim3(256), 0, st, (const uint4*)x, idx, count,
+                               T, cpr, scale, (uint4*)out);
+        else
+            hipLaunchKernelGGL(gather_rows_f32_scaled_kernel, grid, dim3(256), 0, st, (const float4*)x, idx, count,
+                               T, cpr, scale, (float4*)out);
         SCFA_HIP_TRY(hipGetLastError());
         return SCFA_OK;
     }

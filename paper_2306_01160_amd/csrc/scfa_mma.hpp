@@ -23,6 +23,7 @@ using f32x16 = float __attribute__((ext_vector_type(16)));
 using i16x4 = short __attribute__((ext_vector_type(4)));
 
 constexpr float LOG2E = 1.4426950408889634f;
+constexpr float LN2 = 0.6931471805599453f;
 
 __device__ __forceinline__ f16x8 as_f16x8(uint4 v) { return __builtin_bit_cast(f16x8, v); }
 

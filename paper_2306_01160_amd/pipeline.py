@@ -59,7 +59,7 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
     q_idx, q_bs, q_off = sc.scfa_sort_by_bucket(_seg(bucket_q), nb)
     k_idx, k_bs, k_off = sc.scfa_sort_by_bucket(_seg(bucket_k), nb)
     f16 = q.dtype == torch.bfloat16
-    q_p = sc.scfa_gather_rows(_seg(q), q_idx, to_f16=f16)
+    q_p = sc.scfa_gather_rows(_seg(q), q_idx, to_f16=f16, scale=sc.scfa_q_scale(sm_scale))
     k_p = sc.scfa_gather_rows(_seg(k), k_idx, to_f16=f16)
     v_p = sc.scfa_gather_rows(_seg(v), k_idx, to_f16=f16)
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
@@ -84,7 +84,7 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True):
     q_idx, n_q = sc.scfa_compact_keep(_seg(keep_q))
     k_idx, n_k = sc.scfa_compact_keep(_seg(keep_k))
     f16 = q.dtype == torch.bfloat16
-    q_c = sc.scfa_gather_rows(_seg(q), q_idx, n_q, to_f16=f16)
+    q_c = sc.scfa_gather_rows(_seg(q), q_idx, n_q, to_f16=f16, scale=sc.scfa_q_scale(sm_scale))
     k_c = sc.scfa_gather_rows(_seg(k), k_idx, n_k, to_f16=f16)
     v_c = sc.scfa_gather_rows(_seg(v), k_idx, n_k, to_f16=f16)
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_QKDROP, q_idx, k_idx, n_q, n_k, 1, tiles,
