@@ -83,6 +83,15 @@ int scfa_sort_by_bucket(const int32_t *bucket, int S, int T, int nb,
                         int32_t *idx_out, int32_t *bucket_sorted_out,
                         int32_t *bucket_off_out, void *stream);
 
+/* The same sort for the query and the key bucket ids of one attention call in ONE
+ * launch (Sec. 3.2 sorts both); outputs as above, one set per side.  The *_sorted_out
+ * pointers are nullable. */
+int scfa_sort_by_bucket_pair(const int32_t *bucket_q, const int32_t *bucket_k,
+                             int S, int T, int nb,
+                             int32_t *q_idx_out, int32_t *q_sorted_out, int32_t *q_off_out,
+                             int32_t *k_idx_out, int32_t *k_sorted_out, int32_t *k_off_out,
+                             void *stream);
+
 /* ------------------------------------------------------------------------
  * a2. Compaction for QK-dropping (Sec. 3.1, "Shrinking the attention matrix").
  *
@@ -95,6 +104,11 @@ int scfa_sort_by_bucket(const int32_t *bucket, int S, int T, int nb,
 int scfa_compact_keep(const uint8_t *keep, int S, int T,
                       int32_t *idx_out, int32_t *count_out, void *stream);
 
+/* Query and key keep flags of one attention call compacted in ONE launch. */
+int scfa_compact_keep_pair(const uint8_t *keep_q, const uint8_t *keep_k, int S, int T,
+                           int32_t *q_idx_out, int32_t *n_q_out,
+                           int32_t *k_idx_out, int32_t *n_k_out, void *stream);
+
 /* ------------------------------------------------------------------------
  * a3. Row gather: out[s,r,:] = x[s, idx[s,r], :] for r < n[s], where n[s] =
  * count[s] if `count` is non-null, else T.  Rows r >= n[s] of `out` are not
@@ -106,8 +120,8 @@ int scfa_compact_keep(const uint8_t *keep, int S, int T,
  * the attention kernels.  bf16 -> fp16 rounds to nearest even; it is exact for
  * magnitudes in [2^-17, 65504], smaller ones lose low bits (absolute error < 2^-25),
  * larger ones saturate at 65504.
- * scale: every element is multiplied by `scale` before the single rounding to
- * out_dtype.  scale == 1 with out_dtype == dtype is a bit-exact copy; bf16 -> bf16
+ * scale: every element is multiplied by `scale` in fp32 and the product is then
+ * converted to out_dtype.  scale == 1 with out_dtype == dtype is a bit-exact copy; bf16 -> bf16
  * with another scale is SCFA_EUNSUPPORTED.  The attention entry points expect the
  * QUERIES gathered with scale = scfa_q_scale(sm_scale) = sm_scale * log2(e) (their
  * score contraction then yields base-2 exponents directly, see b.); keys, values
@@ -117,6 +131,16 @@ float scfa_q_scale(float sm_scale);
 int scfa_gather_rows(const void *x, const int32_t *idx, const int32_t *count,
                      int S, int T, int d, int dtype, int out_dtype, float scale,
                      void *out, void *stream);
+
+/* Q, K and V of one attention call gathered in ONE launch: q_out = q_scale * q[q_idx]
+ * (rows < n_q[s]), k_out = k[k_idx], v_out = v[k_idx] (rows < n_k[s]); n_q / n_k
+ * nullable (= T).  Same dtype rules as scfa_gather_rows; pass q_scale =
+ * scfa_q_scale(sm_scale) for the attention entry points. */
+int scfa_gather_qkv(const void *q, const void *k, const void *v,
+                    const int32_t *q_idx, const int32_t *k_idx,
+                    const int32_t *n_q, const int32_t *n_k,
+                    int S, int T, int d, int dtype, int out_dtype, float q_scale,
+                    void *q_out, void *k_out, void *v_out, void *stream);
 
 /* ------------------------------------------------------------------------
  * a4. Tile-skip schedule.  The paper finds, per block of queries, the range of

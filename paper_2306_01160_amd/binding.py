@@ -26,6 +26,7 @@ KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_
 
 EXPORTS = [
     "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket",
+    "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv",
     "scfa_compact_keep", "scfa_q_scale", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
     "scfa_attn_bwd_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
@@ -53,6 +54,9 @@ def lib():
         L.scfa_error_string.argtypes = [ci]
         L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp]
+        L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+        L.scfa_compact_keep_pair.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
+        L.scfa_gather_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
         L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp]
         L.scfa_q_scale.argtypes = [ctypes.c_float]
         L.scfa_q_scale.restype = ctypes.c_float
@@ -145,6 +149,43 @@ def scfa_compact_keep(keep: torch.Tensor):
     count = torch.empty((S,), dtype=torch.int32, device=keep.device)
     _check(lib().scfa_compact_keep(_ptr(keep), S, T, _ptr(idx), _ptr(count), _stream()), "scfa_compact_keep")
     return idx, count
+
+
+def scfa_sort_by_bucket_pair(bucket_q: torch.Tensor, bucket_k: torch.Tensor, nb: int, want_sorted=True):
+    """Both sides of one attention call in one launch -> (q_idx, q_sorted, q_off), (k_idx, k_sorted, k_off)."""
+    S, T = bucket_q.shape
+    assert bucket_k.shape == bucket_q.shape
+    both = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device)
+    srt = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device) if want_sorted else None
+    off = torch.empty((2, S, nb + 1), dtype=torch.int32, device=bucket_q.device)
+    _check(lib().scfa_sort_by_bucket_pair(_ptr(bucket_q), _ptr(bucket_k), S, T, nb, _ptr(both[0]),
+                                          _ptr(srt[0]) if want_sorted else None, _ptr(off[0]), _ptr(both[1]),
+                                          _ptr(srt[1]) if want_sorted else None, _ptr(off[1]), _stream()),
+           "scfa_sort_by_bucket_pair")
+    return (both[0], srt[0] if want_sorted else None, off[0]), (both[1], srt[1] if want_sorted else None, off[1])
+
+
+def scfa_compact_keep_pair(keep_q: torch.Tensor, keep_k: torch.Tensor):
+    """Both sides of one attention call in one launch -> (q_idx, n_q), (k_idx, n_k)."""
+    S, T = keep_q.shape
+    assert keep_k.shape == keep_q.shape
+    idx = torch.empty((2, S, T), dtype=torch.int32, device=keep_q.device)
+    cnt = torch.empty((2, S), dtype=torch.int32, device=keep_q.device)
+    _check(lib().scfa_compact_keep_pair(_ptr(keep_q), _ptr(keep_k), S, T, _ptr(idx[0]), _ptr(cnt[0]), _ptr(idx[1]),
+                                        _ptr(cnt[1]), _stream()), "scfa_compact_keep_pair")
+    return (idx[0], cnt[0]), (idx[1], cnt[1])
+
+
+def scfa_gather_qkv(q, k, v, q_idx, k_idx, n_q=None, n_k=None, to_f16=False, q_scale=1.0):
+    """Permuted / compacted Q (times q_scale), K, V in one launch; inputs [S,T,d]."""
+    S, T, d = q.shape
+    odt = torch.float16 if to_f16 else q.dtype
+    out = torch.empty((3, S, T, d), dtype=odt, device=q.device)
+    out_code = SCFA_F16 if to_f16 else dtype_code(q)
+    _check(lib().scfa_gather_qkv(_ptr(q), _ptr(k), _ptr(v), _ptr(q_idx), _ptr(k_idx), _ptr(n_q), _ptr(n_k), S, T, d,
+                                 dtype_code(q), out_code, float(q_scale), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
+                                 _stream()), "scfa_gather_qkv")
+    return out[0], out[1], out[2]
 
 
 def scfa_q_scale(tau: float) -> float:

@@ -120,8 +120,8 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
     w += align_up((size_t)S * T * 4, 256);
     void* aux_perm = w;                         // [S,T,8] fp16: pieces of LSE log2 e and D
     w += align_up((size_t)S * T * 16, 256);
-    uint32_t* amax = reinterpret_cast<uint32_t*>(w);
-    w += align_up((size_t)S * 4, 256);
+    uint32_t* amax = reinterpret_cast<uint32_t*>(w);   // [S,64] partial maxima of |dO|
+    w += align_up((size_t)S * 64 * 4, 256);
     float* inv_scale = reinterpret_cast<float*>(w);
 
     if (qkdrop) {
@@ -166,13 +166,33 @@ int scfa_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* id
 {
     if (!bucket || !idx_out || !bucket_off_out || S <= 0 || T <= 0 || nb <= 0) return SCFA_EINVAL;
     if (nb > SCFA_MAX_BUCKETS || S > 0x7fffffff / 1) return SCFA_EUNSUPPORTED;
-    return launch_sort_by_bucket(bucket, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, (hipStream_t)stream);
+    return launch_sort_by_bucket(1, bucket, nullptr, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, nullptr,
+                                 nullptr, nullptr, (hipStream_t)stream);
+}
+
+int scfa_sort_by_bucket_pair(const int32_t* bucket_q, const int32_t* bucket_k, int S, int T, int nb,
+                             int32_t* q_idx_out, int32_t* q_sorted_out, int32_t* q_off_out, int32_t* k_idx_out,
+                             int32_t* k_sorted_out, int32_t* k_off_out, void* stream)
+{
+    if (!bucket_q || !bucket_k || !q_idx_out || !q_off_out || !k_idx_out || !k_off_out || S <= 0 || T <= 0 || nb <= 0)
+        return SCFA_EINVAL;
+    if (nb > SCFA_MAX_BUCKETS || S > 0x3fffffff) return SCFA_EUNSUPPORTED;
+    return launch_sort_by_bucket(2, bucket_q, bucket_k, S, T, nb, q_idx_out, q_sorted_out, q_off_out, k_idx_out,
+                                 k_sorted_out, k_off_out, (hipStream_t)stream);
 }
 
 int scfa_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out, void* stream)
 {
     if (!keep || !idx_out || !count_out || S <= 0 || T <= 0) return SCFA_EINVAL;
-    return launch_compact_keep(keep, S, T, idx_out, count_out, (hipStream_t)stream);
+    return launch_compact_keep(1, keep, nullptr, S, T, idx_out, count_out, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int scfa_compact_keep_pair(const uint8_t* keep_q, const uint8_t* keep_k, int S, int T, int32_t* q_idx_out,
+                           int32_t* n_q_out, int32_t* k_idx_out, int32_t* n_k_out, void* stream)
+{
+    if (!keep_q || !keep_k || !q_idx_out || !n_q_out || !k_idx_out || !n_k_out || S <= 0 || T <= 0) return SCFA_EINVAL;
+    if (S > 0x3fffffff) return SCFA_EUNSUPPORTED;
+    return launch_compact_keep(2, keep_q, keep_k, S, T, q_idx_out, n_q_out, k_idx_out, n_k_out, (hipStream_t)stream);
 }
 
 float scfa_q_scale(float tau) { return tau * 1.4426950408889634f; }
@@ -188,7 +208,35 @@ int scfa_gather_rows(const void* x, const int32_t* idx, const int32_t* count, in
     const long long row_bytes = (long long)d * (dtype == SCFA_BF16 ? 2 : 4);
     if (row_bytes % 16 != 0 || !aligned16(x) || !aligned16(out)) return SCFA_EINVAL;
     if (S > 65535 || (long long)T * (row_bytes / 16) / 256 > 0x7fffffffLL) return SCFA_EUNSUPPORTED;
-    return launch_gather_rows(x, idx, count, S, T, (int)row_bytes, mode, scale, out, (hipStream_t)stream);
+    const void* xs[1] = {x};
+    const int32_t* is[1] = {idx};
+    const int32_t* cs[1] = {count};
+    void* os[1] = {out};
+    return launch_gather_rows(1, xs, is, cs, &scale, os, S, T, (int)row_bytes, mode, (hipStream_t)stream);
+}
+
+int scfa_gather_qkv(const void* q, const void* k, const void* v, const int32_t* q_idx, const int32_t* k_idx,
+                    const int32_t* n_q, const int32_t* n_k, int S, int T, int d, int dtype, int out_dtype,
+                    float q_scale, void* q_out, void* k_out, void* v_out, void* stream)
+{
+    if (!q || !k || !v || !q_idx || !k_idx || !q_out || !k_out || !v_out || S <= 0 || T <= 0 || d <= 0 ||
+        !(q_scale == q_scale))
+        return SCFA_EINVAL;
+    if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
+    if (out_dtype != dtype && !(dtype == SCFA_BF16 && out_dtype == SCFA_F16)) return SCFA_EUNSUPPORTED;
+    if (q_scale != 1.0f && dtype == SCFA_BF16 && out_dtype == SCFA_BF16) return SCFA_EUNSUPPORTED;
+    const int mode = out_dtype != dtype ? 1 : (dtype == SCFA_F32 ? 2 : 0);
+    const long long row_bytes = (long long)d * (dtype == SCFA_BF16 ? 2 : 4);
+    if (row_bytes % 16 != 0 || !aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(q_out) ||
+        !aligned16(k_out) || !aligned16(v_out))
+        return SCFA_EINVAL;
+    if (S > 65535 || (long long)T * (row_bytes / 16) / 256 > 0x7fffffffLL) return SCFA_EUNSUPPORTED;
+    const void* xs[3] = {q, k, v};
+    const int32_t* is[3] = {q_idx, k_idx, k_idx};
+    const int32_t* cs[3] = {n_q, n_k, n_k};
+    const float sc[3] = {q_scale, 1.0f, 1.0f};
+    void* os[3] = {q_out, k_out, v_out};
+    return launch_gather_rows(3, xs, is, cs, sc, os, S, T, (int)row_bytes, mode, (hipStream_t)stream);
 }
 
 int scfa_num_work_items(int T, int nb, int tile)
@@ -255,7 +303,7 @@ size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype)
 {
     if (S <= 0 || T <= 0 || d <= 0 || dtype != SCFA_BF16) return 0;
     return align_up((size_t)S * T * d * 2, 256) + 2 * align_up((size_t)S * T * 4, 256) +
-           align_up((size_t)S * T * 16, 256) + 2 * align_up((size_t)S * 4, 256);
+           align_up((size_t)S * T * 16, 256) + align_up((size_t)S * 64 * 4, 256) + align_up((size_t)S * 4, 256);
 }
 
 int scfa_hash_attn_bwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,

@@ -37,20 +37,31 @@ namespace scfa {
 // ===========================================================================
 // Pre-pass
 // ===========================================================================
-__global__ __launch_bounds__(256) void fill_u32_kernel(uint32_t* p, int n, uint32_t v)
-{
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n) p[i] = v;
-}
+constexpr int AMAX_BLOCKS = 64;   // partial maxima per segment
 
-// amax[s] = max |dO[s]| as float bits (non-negative floats order like unsigned integers)
+// partial[s][blockIdx.x] = max |dO| over this workgroup's share of segment s, as float bits
+// (non-negative floats order like unsigned integers).  No atomics, no initialisation.
 __global__ __launch_bounds__(256) void dout_amax_kernel(const uint4* __restrict__ d_o, long long chunks_per_seg,
-                                                        uint32_t* __restrict__ amax)
+                                                        uint32_t* __restrict__ partial)
 {
     const int s = blockIdx.y;
     const uint4* p = d_o + (size_t)s * chunks_per_seg;
     uint32_t m = 0;
-    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < chunks_per_seg; i += (long long)gridDim.x * 256) {
+    const long long stride = (long long)gridDim.x * 256;
+    long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+    for (; i + 3 * stride < chunks_per_seg; i += 4 * stride) {   // four independent loads in flight
+        const uint4 v[4] = {p[i], p[i + stride], p[i + 2 * stride], p[i + 3 * stride]};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                m = max(m, (w[j] << 16) & 0x7fffffffu);
+                m = max(m, w[j] & 0x7fff0000u);
+            }
+        }
+    }
+    for (; i < chunks_per_seg; i += stride) {
         const uint4 v = p[i];
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
@@ -64,10 +75,8 @@ __global__ __launch_bounds__(256) void dout_amax_kernel(const uint4* __restrict_
     __shared__ uint32_t wave_max[4];
     if ((threadIdx.x & 63) == 0) wave_max[threadIdx.x >> 6] = m;
     __syncthreads();
-    if (threadIdx.x == 0) {   // one atomic per workgroup: the [S] targets are heavily shared
-        m = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
-        if (m != 0) atomicMax(&amax[s], m);
-    }
+    if (threadIdx.x == 0)
+        partial[(size_t)s * AMAX_BLOCKS + blockIdx.x] = max(max(wave_max[0], wave_max[1]), max(wave_max[2], wave_max[3]));
 }
 
 // power-of-two scale that brings a magnitude with these float bits into [1, 2)
@@ -100,8 +109,8 @@ __device__ __forceinline__ void split3(float x, uint32_t& w01, uint32_t& w23)
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const uint16_t* __restrict__ o, const float* __restrict__ o_f32, const float* __restrict__ lse,
-    const uint16_t* __restrict__ d_o, const int32_t* __restrict__ q_idx, const uint32_t* __restrict__ amax,
-    int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
+    const uint16_t* __restrict__ d_o, const int32_t* __restrict__ q_idx, const uint32_t* __restrict__ amax_partial,
+    int n_partial, int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
     uint16_t* __restrict__ aux_perm, float* __restrict__ inv_scale_out)
 {
     constexpr int LPR = D / 8;   // lanes per row
@@ -110,8 +119,16 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const int r = (blockIdx.x * 256 + threadIdx.x) / LPR;
     const int c8 = threadIdx.x % LPR;
     const bool valid = r < T;
+    __shared__ uint32_t s_amax;
+    if (threadIdx.x < 64) {   // reduce the segment's partial maxima
+        uint32_t m = (int)threadIdx.x < n_partial ? amax_partial[(size_t)s * AMAX_BLOCKS + threadIdx.x] : 0u;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off));
+        if (threadIdx.x == 0) s_amax = m;
+    }
+    __syncthreads();
     float scale, inv_scale;
-    pow2_scales(amax[s], scale, inv_scale);
+    pow2_scales(s_amax, scale, inv_scale);
     if (blockIdx.x == 0 && threadIdx.x == 0) inv_scale_out[s] = inv_scale;
     float acc = 0.f;
     int src = 0;
@@ -168,19 +185,18 @@ int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, co
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_PREP, st);
-    hipLaunchKernelGGL(fill_u32_kernel, dim3((S + 255) / 256), dim3(256), 0, st, amax, S, 0u);
     const long long chunks = (long long)T * d / 8;
     const long long want = (chunks + 256 * 8 - 1) / (256 * 8);
-    const unsigned nblk = (unsigned)(want < 64 ? want : 64);
+    const unsigned nblk = (unsigned)(want < AMAX_BLOCKS ? want : AMAX_BLOCKS);
     hipLaunchKernelGGL(dout_amax_kernel, dim3(nblk, S), dim3(256), 0, st, (const uint4*)d_o, chunks, amax);
     const long long threads = (long long)T * (d / 8);
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
     if (d == 64)
         hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
-                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_idx, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else if (d == 128)
         hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
-                           q_idx, amax, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_idx, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());

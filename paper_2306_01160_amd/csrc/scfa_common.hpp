@@ -49,12 +49,13 @@ constexpr int F32_TILE_M = 64;   // fp32 path: one thread per query row
 constexpr int F32_TILE_N = 32;
 
 // ---- kernel launchers (defined in the .hip files) ---------------------------
-int launch_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
-                          int32_t* bucket_sorted_out, int32_t* off_out, hipStream_t st);
-int launch_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out,
-                        hipStream_t st);
-int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
-                       int row_bytes, int mode, float scale, void* out, hipStream_t st);
+int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
+                          int32_t* idx0, int32_t* sorted0, int32_t* off0, int32_t* idx1, int32_t* sorted1,
+                          int32_t* off1, hipStream_t st);
+int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
+                        int32_t* count0, int32_t* idx1, int32_t* count1, hipStream_t st);
+int launch_gather_rows(int n_tensors, const void* const* x, const int32_t* const* idx, const int32_t* const* count,
+                       const float* scale, void* const* out, int S, int T, int row_bytes, int mode, hipStream_t st);
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
                         int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,

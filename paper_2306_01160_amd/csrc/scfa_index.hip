@@ -29,15 +29,30 @@ __device__ __forceinline__ int load_key(const void* keys, size_t i, int nb)
 
 // keys: [S,T] int32 bucket ids, or uint8 keep flags in KEEP_MODE (key 0 = kept, 1 = dropped).
 // off_out: [S,nb+1] in bucket mode; [S] kept count in KEEP_MODE.
+// One launch sorts up to two independent key tensors (queries and keys of the same shape):
+// workgroups [0, S) take problem 0, workgroups [S, 2S) problem 1.
+struct SortProblem {
+    const void* keys;
+    int32_t* idx_out;
+    int32_t* key_sorted_out;
+    int32_t* off_out;
+};
+
+constexpr int SORT_PREFETCH = 16;  // 64-token steps whose keys are loaded together
+
 template <bool KEEP_MODE>
 __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
-    const void* __restrict__ keys, int T, int nb, int nbits, int32_t* __restrict__ idx_out,
-    int32_t* __restrict__ key_sorted_out, int32_t* __restrict__ off_out)
+    SortProblem p0, SortProblem p1, int S, int T, int nb, int nbits)
 {
     extern __shared__ int32_t smem[];
     int32_t* hist = smem;                       // [SORT_WAVES][nb]  counts, then running bases
     int32_t* tot = smem + SORT_WAVES * nb;      // [nb+1]
-    const int s = blockIdx.x;
+    const bool second = (int)blockIdx.x >= S;
+    const int s = second ? blockIdx.x - S : blockIdx.x;
+    const void* __restrict__ keys = second ? p1.keys : p0.keys;
+    int32_t* __restrict__ idx_out = second ? p1.idx_out : p0.idx_out;
+    int32_t* __restrict__ key_sorted_out = second ? p1.key_sorted_out : p0.key_sorted_out;
+    int32_t* __restrict__ off_out = second ? p1.off_out : p0.off_out;
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const size_t seg = (size_t)s * T;
@@ -50,7 +65,21 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
 
     for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] = 0;
     __syncthreads();
-    for (int t = r0 + lane; t < r1; t += 64) atomicAdd(&hist[wave * nb + load_key<KEEP_MODE>(keys, seg + t, nb)], 1);
+    // histogram of the run; the keys of SORT_PREFETCH 64-token steps are loaded together so
+    // that the memory latency is paid once per group, not once per step.  A run of at most
+    // one group (T <= 16 * 64 * SORT_PREFETCH) keeps its keys in registers for the ranking.
+    const bool single_group = r1 - r0 <= 64 * SORT_PREFETCH;
+    int keyv[SORT_PREFETCH];
+    for (int g0 = r0; g0 < r1; g0 += 64 * SORT_PREFETCH) {
+#pragma unroll
+        for (int u = 0; u < SORT_PREFETCH; ++u) {
+            const int t = g0 + 64 * u + lane;
+            keyv[u] = t < r1 ? load_key<KEEP_MODE>(keys, seg + t, nb) : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < SORT_PREFETCH; ++u)
+            if (keyv[u] >= 0) atomicAdd(&hist[wave * nb + keyv[u]], 1);
+    }
     __syncthreads();
 
     // per key: exclusive prefix over wavefronts (in place) and the key total
@@ -82,148 +111,137 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
     for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] += tot[i % nb];
     __syncthreads();
 
-    // rank and scatter, 64 consecutive tokens per step
+    // rank and scatter, 64 consecutive tokens per step, keys again loaded a group at a time
     int32_t* base = hist + wave * nb;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int t0 = r0; t0 < r1; t0 += 64) {
-        const int t = t0 + lane;
-        const bool valid = t < r1;
-        const int key = valid ? load_key<KEEP_MODE>(keys, seg + t, nb) : 0;
-        unsigned long long same = __ballot(valid);
-        for (int b = 0; b < nbits; ++b) {
-            const bool bit = (key >> b) & 1;
-            const unsigned long long m = __ballot(bit);
-            same &= bit ? m : ~m;
+    for (int g0 = r0; g0 < r1; g0 += 64 * SORT_PREFETCH) {
+        if (!single_group) {
+#pragma unroll
+            for (int u = 0; u < SORT_PREFETCH; ++u) {
+                const int t = g0 + 64 * u + lane;
+                keyv[u] = t < r1 ? load_key<KEEP_MODE>(keys, seg + t, nb) : -1;
+            }
         }
-        const int rank = __popcll(same & lt_mask);
-        const int cnt = __popcll(same);
-        int pos = 0;
-        if (valid) pos = base[key] + rank;
-        __builtin_amdgcn_wave_barrier();
-        if (valid && rank == 0) base[key] += cnt;
-        __builtin_amdgcn_wave_barrier();
-        if (valid) {
-            idx_out[seg + pos] = t;
-            if (key_sorted_out) key_sorted_out[seg + pos] = key;
+#pragma unroll
+        for (int u = 0; u < SORT_PREFETCH; ++u) {
+            const int t = g0 + 64 * u + lane;
+            if (g0 + 64 * u >= r1) break;       // wave-uniform
+            const bool valid = t < r1;
+            const int key = valid ? keyv[u] : 0;
+            unsigned long long same = __ballot(valid);
+            for (int b = 0; b < nbits; ++b) {
+                const bool bit = (key >> b) & 1;
+                const unsigned long long m = __ballot(bit);
+                same &= bit ? m : ~m;
+            }
+            const int rank = __popcll(same & lt_mask);
+            const int cnt = __popcll(same);
+            int pos = 0;
+            if (valid) pos = base[key] + rank;
+            __builtin_amdgcn_wave_barrier();
+            if (valid && rank == 0) base[key] += cnt;
+            __builtin_amdgcn_wave_barrier();
+            if (valid) {
+                idx_out[seg + pos] = t;
+                if (key_sorted_out) key_sorted_out[seg + pos] = key;
+            }
         }
     }
 }
 
-int launch_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
-                          int32_t* bucket_sorted_out, int32_t* off_out, hipStream_t st)
+// n_problems: 1 or 2 (bucket1 etc. ignored for 1)
+int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
+                          int32_t* idx0, int32_t* sorted0, int32_t* off0, int32_t* idx1, int32_t* sorted1,
+                          int32_t* off1, hipStream_t st)
 {
     int nbits = 0;
     while ((1 << nbits) < nb) ++nbits;
     const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
+    const SortProblem p0{bucket0, idx0, sorted0, off0}, p1{bucket1, idx1, sorted1, off1};
     ProfScope prof(SCFA_K_SORT, st);
-    hipLaunchKernelGGL(stable_sort_small_keys_kernel<false>, dim3(S), dim3(SORT_THREADS), smem, st,
-                       bucket, T, nb, nbits, idx_out, bucket_sorted_out, off_out);
+    hipLaunchKernelGGL(stable_sort_small_keys_kernel<false>, dim3(S * n_problems), dim3(SORT_THREADS), smem, st,
+                       p0, p1, S, T, nb, nbits);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
-int launch_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out,
-                        hipStream_t st)
+int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
+                        int32_t* count0, int32_t* idx1, int32_t* count1, hipStream_t st)
 {
     const int nb = 2;
     const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
+    const SortProblem p0{keep0, idx0, nullptr, count0}, p1{keep1, idx1, nullptr, count1};
     ProfScope prof(SCFA_K_COMPACT, st);
-    hipLaunchKernelGGL(stable_sort_small_keys_kernel<true>, dim3(S), dim3(SORT_THREADS), smem, st,
-                       keep, T, nb, 1, idx_out, (int32_t*)nullptr, count_out);
+    hipLaunchKernelGGL(stable_sort_small_keys_kernel<true>, dim3(S * n_problems), dim3(SORT_THREADS), smem, st,
+                       p0, p1, S, T, nb, 1);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
 // ---------------------------------------------------------------------------
 // Row gather: 16 bytes per thread, a row of d elements is row_bytes/16 consecutive
-// lanes, so every row is read and written as whole cache lines.
-__global__ __launch_bounds__(256) void gather_rows_kernel(const uint4* __restrict__ x,
-                                                          const int32_t* __restrict__ idx,
-                                                          const int32_t* __restrict__ count, int T,
-                                                          int chunks_per_row, uint4* __restrict__ out)
-{
-    const int s = blockIdx.y;
-    const int n = count ? count[s] : T;
-    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
-    const int r = (int)(g / chunks_per_row);
-    const int c = (int)(g % chunks_per_row);
-    if (r >= n) return;
-    const int src = idx[(size_t)s * T + r];
-    out[((size_t)s * T + r) * chunks_per_row + c] = x[((size_t)s * T + src) * chunks_per_row + c];
-}
+// lanes, so every row is read and written as whole cache lines.  One launch serves up to
+// three tensors of the same shape (blockIdx.z): Q, K and V of one attention call.
+struct GatherProblem {
+    const void* x;
+    const int32_t* idx;
+    const int32_t* count;
+    void* out;
+    float scale;
+};
+struct GatherBatch { GatherProblem p[3]; };
 
-// Same gather for bf16 rows, multiplying by `scale` and converting to fp16 on the way (one
-// rounding to nearest even; with scale 1 exact for magnitudes in [2^-17, 65504]; larger
-// results saturate to the largest fp16).
-__global__ __launch_bounds__(256) void gather_rows_bf16_to_f16_kernel(const uint4* __restrict__ x,
-                                                                      const int32_t* __restrict__ idx,
-                                                                      const int32_t* __restrict__ count, int T,
-                                                                      int chunks_per_row, float scale,
-                                                                      uint4* __restrict__ out)
+// MODE 0: bit-exact copy; 1: bf16 -> fp16 (times scale, one rounding to nearest even; with
+// scale 1 exact for magnitudes in [2^-17, 65504], larger results saturate to the largest
+// fp16); 2: fp32 times scale (one rounding)
+template <int MODE>
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherBatch batch, int T, int chunks_per_row)
 {
+    const GatherProblem& pr = batch.p[blockIdx.z];
     const int s = blockIdx.y;
-    const int n = count ? count[s] : T;
+    const int n = pr.count ? pr.count[s] : T;
     const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
     const int r = (int)(g / chunks_per_row);
     const int c = (int)(g % chunks_per_row);
     if (r >= n) return;
-    const int src = idx[(size_t)s * T + r];
-    const uint4 v = x[((size_t)s * T + src) * chunks_per_row + c];
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-    uint32_t o[4];
+    const int src = pr.idx[(size_t)s * T + r];
+    const uint4 v = reinterpret_cast<const uint4*>(pr.x)[((size_t)s * T + src) * chunks_per_row + c];
+    uint4 res = v;
+    if (MODE == 1) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        uint32_t o[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        float lo = __uint_as_float(w[i] << 16) * scale, hi = __uint_as_float(w[i] & 0xffff0000u) * scale;
-        lo = fminf(fmaxf(lo, -65504.f), 65504.f);
-        hi = fminf(fmaxf(hi, -65504.f), 65504.f);
-        const _Float16 a = (_Float16)lo, b = (_Float16)hi;
-        o[i] = (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+        for (int i = 0; i < 4; ++i) {
+            float lo = __uint_as_float(w[i] << 16) * pr.scale, hi = __uint_as_float(w[i] & 0xffff0000u) * pr.scale;
+            lo = fminf(fmaxf(lo, -65504.f), 65504.f);
+            hi = fminf(fmaxf(hi, -65504.f), 65504.f);
+            const _Float16 a = (_Float16)lo, b = (_Float16)hi;
+            o[i] = (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
+        }
+        res = make_uint4(o[0], o[1], o[2], o[3]);
+    } else if (MODE == 2) {
+        res = make_uint4(__float_as_uint(__uint_as_float(v.x) * pr.scale), __float_as_uint(__uint_as_float(v.y) * pr.scale),
+                         __float_as_uint(__uint_as_float(v.z) * pr.scale), __float_as_uint(__uint_as_float(v.w) * pr.scale));
     }
-    out[((size_t)s * T + r) * chunks_per_row + c] = make_uint4(o[0], o[1], o[2], o[3]);
+    reinterpret_cast<uint4*>(pr.out)[((size_t)s * T + r) * chunks_per_row + c] = res;
 }
 
-// fp32 rows multiplied by `scale` (one rounding)
-__global__ __launch_bounds__(256) void gather_rows_f32_scaled_kernel(const float4* __restrict__ x,
-                                                                     const int32_t* __restrict__ idx,
-                                                                     const int32_t* __restrict__ count, int T,
-                                                                     int chunks_per_row, float scale,
-                                                                     float4* __restrict__ out)
+// mode as in the kernel; n_tensors 1..3 problems of identical shape
+int launch_gather_rows(int n_tensors, const void* const* x, const int32_t* const* idx, const int32_t* const* count,
+                       const float* scale, void* const* out, int S, int T, int row_bytes, int mode, hipStream_t st)
 {
-    const int s = blockIdx.y;
-    const int n = count ? count[s] : T;
-    const long long g = (long long)blockIdx.x * 256 + threadIdx.x;
-    const int r = (int)(g / chunks_per_row);
-    const int c = (int)(g % chunks_per_row);
-    if (r >= n) return;
-    const int src = idx[(size_t)s * T + r];
-    const float4 v = x[((size_t)s * T + src) * chunks_per_row + c];
-    out[((size_t)s * T + r) * chunks_per_row + c] = make_float4(v.x * scale, v.y * scale, v.z * scale, v.w * scale);
-}
-
-// mode: 0 = bit-exact copy, 1 = bf16 -> scaled fp16, 2 = scaled fp32
-int launch_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T,
-                       int row_bytes, int mode, float scale, void* out, hipStream_t st)
-{
-    if (mode != 0) {
-        const int cpr = row_bytes / 16;
-        const long long total = (long long)T * cpr;
-        dim3 grid((unsigned)((total + 255) / 256), S);
-        ProfScope prof(SCFA_K_GATHER, st);
-        if (mode == 1)
-            hipLaunchKernelGGL(gather_rows_bf16_to_f16_kernel, grid, dim3(256), 0, st, (const uint4*)x, idx, count,
-                               T, cpr, scale, (uint4*)out);
-        else
-            hipLaunchKernelGGL(gather_rows_f32_scaled_kernel, grid, dim3(256), 0, st, (const float4*)x, idx, count,
-                               T, cpr, scale, (float4*)out);
-        SCFA_HIP_TRY(hipGetLastError());
-        return SCFA_OK;
-    }
+    GatherBatch batch{};
+    for (int i = 0; i < n_tensors; ++i) batch.p[i] = GatherProblem{x[i], idx[i], count[i], out[i], scale[i]};
     const int cpr = row_bytes / 16;
     const long long total = (long long)T * cpr;
-    dim3 grid((unsigned)((total + 255) / 256), S);
+    dim3 grid((unsigned)((total + 255) / 256), S, n_tensors);
     ProfScope prof(SCFA_K_GATHER, st);
-    hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, st, (const uint4*)x, idx, count, T, cpr,
-                       (uint4*)out);
+    if (mode == 0)
+        hipLaunchKernelGGL(gather_rows_kernel<0>, grid, dim3(256), 0, st, batch, T, cpr);
+    else if (mode == 1)
+        hipLaunchKernelGGL(gather_rows_kernel<1>, grid, dim3(256), 0, st, batch, T, cpr);
+    else
+        hipLaunchKernelGGL(gather_rows_kernel<2>, grid, dim3(256), 0, st, batch, T, cpr);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }

@@ -13,11 +13,15 @@
 //                  (only those with position < largest key position need a mask)
 // Items of a segment are emitted in order of decreasing work so that the long
 // ones are dispatched first.
+//
+// One workgroup builds one list of one segment (the forward and the backward list are
+// independent).  The index vector that is searched is first copied into LDS when it fits,
+// so the dependent steps of the binary searches cost LDS, not global-memory, latency.
 #include "scfa_common.hpp"
 
 namespace scfa {
 
-constexpr int RANGES_THREADS = 256;
+constexpr int RANGES_THREADS = 512;
 
 // number of entries of a[0..n) that are <= v (a increasing)
 __device__ __forceinline__ int count_le(const int32_t* __restrict__ a, int n, int v)
@@ -48,7 +52,7 @@ struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket; };
 //   FORWARD : b range = keys with pos <= max a pos;  extra = #keys with pos <= min a pos
 //   BACKWARD: b range = queries with pos >= min a pos; extra = #queries of the range with pos < max a pos
 template <bool FORWARD>
-__device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* __restrict__ b_idx,
+__device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_idx,
                            const int32_t* a_off, const int32_t* b_off, int nb, int tile_a,
                            int tile_b, int n_items_max, int32_t* __restrict__ work_out,
                            long long* counters2, int32_t* s_tile_base, int32_t* s_cost)
@@ -136,7 +140,7 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* __r
 __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int variant, const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
     const int32_t* __restrict__ q_off_g, const int32_t* __restrict__ k_off_g, int T, int nb,
-    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
+    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int stage_in_lds,
     int32_t* __restrict__ fwd_work, int32_t* __restrict__ bwd_work, long long* __restrict__ counters)
 {
     extern __shared__ int32_t smem[];
@@ -144,7 +148,9 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int32_t* s_koff = s_qoff + nb + 1;        // [nb+1]
     int32_t* s_tile_base = s_koff + nb + 1;   // [nb+1]
     int32_t* s_cost = s_tile_base + nb + 1;   // [max(n_fwd, n_bwd)]
+    int32_t* s_idx = smem + ((3 * (nb + 1) + (n_fwd > n_bwd ? n_fwd : n_bwd) + 3) & ~3);   // [T] when staged, 16-byte aligned
     const int s = blockIdx.x;
+    const bool backward = blockIdx.y == 1;
     if (variant == SCFA_QKDROP) {
         if (threadIdx.x == 0) {
             s_qoff[0] = 0; s_qoff[1] = min(max(q_off_g[s], 0), T);
@@ -156,17 +162,43 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
             s_koff[b] = k_off_g[(size_t)s * (nb + 1) + b];
         }
     }
-    __syncthreads();
     const int32_t* qi = q_idx + (size_t)s * T;
     const int32_t* ki = k_idx + (size_t)s * T;
+    const int32_t* searched = backward ? qi : ki;     // the ranged side
+    if (stage_in_lds) {   // 16-byte loads, eight in flight per thread (the segment base is 16-byte aligned when T % 4 == 0)
+        if ((T & 3) == 0) {
+            const int4* src4 = reinterpret_cast<const int4*>(searched);
+            int4* dst4 = reinterpret_cast<int4*>(s_idx);
+            const int n4 = T >> 2;
+            for (int t0 = 0; t0 < n4; t0 += RANGES_THREADS * 8) {
+                int4 v[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + u * RANGES_THREADS + threadIdx.x;
+                    v[u] = t < n4 ? src4[t] : make_int4(0, 0, 0, 0);
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int t = t0 + u * RANGES_THREADS + threadIdx.x;
+                    if (t < n4) dst4[t] = v[u];
+                }
+            }
+        } else {
+            for (int t = threadIdx.x; t < T; t += RANGES_THREADS) s_idx[t] = searched[t];
+        }
+        searched = s_idx;
+    }
+    __syncthreads();
     long long* cnt = counters ? counters + (size_t)s * 4 : nullptr;
-    build_list<true>(qi, ki, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd,
-                     fwd_work + (size_t)s * n_fwd * WORK_STRIDE, cnt, s_tile_base, s_cost);
-    if (bwd_work)
-        build_list<false>(ki, qi, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd,
+    if (!backward) {
+        build_list<true>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd,
+                         fwd_work + (size_t)s * n_fwd * WORK_STRIDE, cnt, s_tile_base, s_cost);
+        if (!bwd_work && cnt && threadIdx.x == 0) { cnt[2] = 0; cnt[3] = 0; }
+    } else {
+        build_list<false>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd,
                           bwd_work + (size_t)s * n_bwd * WORK_STRIDE, cnt ? cnt + 2 : nullptr,
                           s_tile_base, s_cost);
-    else if (cnt && threadIdx.x == 0) { cnt[2] = 0; cnt[3] = 0; }
+    }
 }
 
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
@@ -175,10 +207,18 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st)
 {
     const int n_max = n_fwd > n_bwd ? n_fwd : n_bwd;
-    const size_t smem = sizeof(int32_t) * (3 * (size_t)(nb + 1) + (size_t)n_max);
+    const size_t small = sizeof(int32_t) * ((3 * (size_t)(nb + 1) + (size_t)n_max + 3) & ~(size_t)3);
+    const int stage = small + sizeof(int32_t) * (size_t)T <= 144 * 1024 ? 1 : 0;
+    const size_t smem = small + (stage ? sizeof(int32_t) * (size_t)T : 0);
+    static bool attr_set = false;
+    if (!attr_set) {
+        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&block_ranges_kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
+        attr_set = true;
+    }
     ProfScope prof(SCFA_K_RANGES, st);
-    hipLaunchKernelGGL(block_ranges_kernel, dim3(S), dim3(RANGES_THREADS), smem, st, variant, q_idx,
-                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, fwd_work,
+    hipLaunchKernelGGL(block_ranges_kernel, dim3(S, bwd_work ? 2 : 1), dim3(RANGES_THREADS), smem, st, variant, q_idx,
+                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, stage, fwd_work,
                        bwd_work, (long long*)counters);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;

@@ -56,12 +56,10 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
     """Hash-sparse attention forward (Sec. 3.2).  Returns (O, LSE, ctx)."""
     B, H, T, d = q.shape
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
-    q_idx, q_bs, q_off = sc.scfa_sort_by_bucket(_seg(bucket_q), nb)
-    k_idx, k_bs, k_off = sc.scfa_sort_by_bucket(_seg(bucket_k), nb)
-    f16 = q.dtype == torch.bfloat16
-    q_p = sc.scfa_gather_rows(_seg(q), q_idx, to_f16=f16, scale=sc.scfa_q_scale(sm_scale))
-    k_p = sc.scfa_gather_rows(_seg(k), k_idx, to_f16=f16)
-    v_p = sc.scfa_gather_rows(_seg(v), k_idx, to_f16=f16)
+    (q_idx, q_bs, q_off), (k_idx, k_bs, k_off) = sc.scfa_sort_by_bucket_pair(_seg(bucket_q), _seg(bucket_k), nb,
+                                                                             want_sorted=False)
+    q_p, k_p, v_p = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, to_f16=q.dtype == torch.bfloat16,
+                                       q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
                                                         want_bwd=need_bwd)
     o_f32 = _o_f32_buffer(q, need_bwd)
@@ -81,12 +79,9 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True):
     """QK-sparse attention forward (Sec. 3.1).  Returns (O, LSE, ctx)."""
     B, H, T, d = q.shape
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
-    q_idx, n_q = sc.scfa_compact_keep(_seg(keep_q))
-    k_idx, n_k = sc.scfa_compact_keep(_seg(keep_k))
-    f16 = q.dtype == torch.bfloat16
-    q_c = sc.scfa_gather_rows(_seg(q), q_idx, n_q, to_f16=f16, scale=sc.scfa_q_scale(sm_scale))
-    k_c = sc.scfa_gather_rows(_seg(k), k_idx, n_k, to_f16=f16)
-    v_c = sc.scfa_gather_rows(_seg(v), k_idx, n_k, to_f16=f16)
+    (q_idx, n_q), (k_idx, n_k) = sc.scfa_compact_keep_pair(_seg(keep_q), _seg(keep_k))
+    q_c, k_c, v_c = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, n_q, n_k,
+                                       to_f16=q.dtype == torch.bfloat16, q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_QKDROP, q_idx, k_idx, n_q, n_k, 1, tiles,
                                                         want_bwd=need_bwd)
     o_f32 = _o_f32_buffer(q, need_bwd)

@@ -106,6 +106,59 @@ def test_gather_rows_bf16_to_f16_compute_format():
     assert torch.equal(out, ref)
 
 
+def test_gather_rows_scaled_queries():
+    """The query gather multiplies by tau * log2(e) before the rounding to the compute format
+    (fp32 product, then one conversion): equals torch's float multiply + conversion bit for bit."""
+    S, T, d = 2, 515, 64
+    rng = np.random.default_rng(11)
+    x = rng.standard_normal((S, T, d)).astype(np.float32)
+    idx = np.stack([rng.permutation(T) for _ in range(S)]).astype(np.int32)
+    scale = sc.scfa_q_scale(0.125)
+    assert scale == float(np.float32(0.125) * np.float32(1.4426950408889634))
+    xb = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
+    g = torch.gather(xb, 1, _t(idx).long()[..., None].expand(-1, -1, d)).float()
+    out = sc.scfa_gather_rows(xb, _t(idx), to_f16=True, scale=scale)
+    assert torch.equal(out, (g * scale).clamp(-65504.0, 65504.0).to(torch.float16))
+    xf = torch.from_numpy(x).to(DEV)
+    gf = torch.gather(xf, 1, _t(idx).long()[..., None].expand(-1, -1, d))
+    assert torch.equal(sc.scfa_gather_rows(xf, _t(idx), scale=scale), gf * scale)
+
+
+@pytest.mark.parametrize("S,T,nb", [(1, 8, 3), (3, 4097, 7), (2, 16384, 8), (5, 1000, 16)])
+def test_pair_entry_points_match_single_calls(S, T, nb):
+    """Query and key side in one launch: same results as two separate calls, bit for bit."""
+    rng = np.random.default_rng(S + T + nb)
+    bq = rng.integers(0, nb, (S, T)).astype(np.int32)
+    bk = rng.integers(0, nb, (S, T)).astype(np.int32)
+    (qi, qs, qo), (ki, ks, ko) = sc.scfa_sort_by_bucket_pair(_t(bq), _t(bk), nb)
+    for got, b in (((qi, qs, qo), bq), ((ki, ks, ko), bk)):
+        ref = oracle.sort_by_bucket(b, nb)
+        for a, r in zip(got, ref):
+            assert np.array_equal(a.cpu().numpy(), r)
+    kq = (rng.random((S, T)) < 0.6).astype(np.uint8)
+    kk = (rng.random((S, T)) < 0.3).astype(np.uint8)
+    (cqi, cnq), (cki, cnk) = sc.scfa_compact_keep_pair(_t(kq), _t(kk))
+    for (gi, gn), keep in (((cqi, cnq), kq), ((cki, cnk), kk)):
+        ri, rn = oracle.compact_keep(keep)
+        assert np.array_equal(gi.cpu().numpy(), ri) and np.array_equal(gn.cpu().numpy(), rn)
+    # fused Q/K/V gather against the single-tensor gather
+    d = 64
+    q, k, v = (torch.from_numpy(rng.standard_normal((S, T, d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
+               for _ in range(3))
+    scale = sc.scfa_q_scale(0.125)
+    for nq_, nk_ in ((None, None), (cnq, cnk)):
+        i_q, i_k = (qi, ki) if nq_ is None else (cqi, cki)
+        sent = [torch.full((S, T, d), 3.0, dtype=torch.float16, device=DEV) for _ in range(3)]
+        r_q = sc.scfa_gather_rows(q, i_q, nq_, out=sent[0].clone(), to_f16=True, scale=scale)
+        r_k = sc.scfa_gather_rows(k, i_k, nk_, out=sent[1].clone(), to_f16=True)
+        r_v = sc.scfa_gather_rows(v, i_k, nk_, out=sent[2].clone(), to_f16=True)
+        g_q, g_k, g_v = sc.scfa_gather_qkv(q, k, v, i_q, i_k, nq_, nk_, to_f16=True, q_scale=scale)
+        for s_ in range(S):
+            a, b = (T, T) if nq_ is None else (int(nq_[s_]), int(nk_[s_]))
+            assert torch.equal(g_q[s_, :a], r_q[s_, :a])
+            assert torch.equal(g_k[s_, :b], r_k[s_, :b]) and torch.equal(g_v[s_, :b], r_v[s_, :b])
+
+
 # ------------------------------------------------------------------ schedule
 
 def _check_schedule(variant, lab_q, lab_k, nb, tiles):
