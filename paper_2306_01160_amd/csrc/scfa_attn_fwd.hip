@@ -12,6 +12,11 @@
 // B-operand layout of O^T += V^T P^T.  V^T comes from the row-major V tile through
 // transposing LDS reads.
 //
+// K / V tiles and the key positions travel global memory -> LDS asynchronously (no
+// registers, no LDS stores), FWD_PREFETCH tiles ahead of the one being computed, into a ring
+// of FWD_PREFETCH + 1 swizzled buffers; one workgroup barrier per tile both publishes the
+// tile that has landed and retires the buffer that is refilled next.
+//
 // The permuted queries arrive multiplied by tau * log2(e), so the contraction yields the
 // scores in base-2 units, x = tau * log2(e) * <q, k>, and no scaling is left per element.
 //
@@ -36,6 +41,13 @@ namespace scfa {
 
 constexpr float LAZY_LOG2 = 6.0f;
 
+// LDS ring of the forward kernel: as many buffers as three resident workgroups allow
+template <int D>
+struct FwdRing {
+    static constexpr int BUF_BYTES = FWD_TILE_N * D * 4 + FWD_TILE_N * 4;
+    static constexpr int NBUF = D == 64 ? 3 : 2;
+};
+
 template <int D, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -47,12 +59,15 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     (void)tau;   // already folded into the permuted queries
     constexpr int BN = FWD_TILE_N;
     constexpr int THREADS = NW * 64;
-    constexpr int KST = D + 8;    // K tile row stride: 16-byte row reads conflict-free
-    constexpr int VST = D + 16;   // V tile row stride: transposing reads conflict-free
+    constexpr int NBUF = FwdRing<D>::NBUF;            // LDS ring; NBUF - 1 tiles are in flight
+    constexpr int TILE_ELEMS = BN * D;
+    constexpr int BUF_BYTES = FwdRing<D>::BUF_BYTES;  // K tile, V tile, key positions
+    constexpr int LOADS_PER_TILE = 2 * AsyncTile<D, BN, THREADS>::ROUNDS + 1;   // per wavefront
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    uint16_t (*Ks)[BN * KST] = reinterpret_cast<uint16_t (*)[BN * KST]>(smem_raw);
-    uint16_t (*Vs)[BN * VST] = reinterpret_cast<uint16_t (*)[BN * VST]>(smem_raw + 2 * BN * KST * 2);
-    int32_t (*kpos_s)[BN] = reinterpret_cast<int32_t (*)[BN]>(smem_raw + 2 * BN * (KST + VST) * 2);
+    auto k_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
+    auto v_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 2); };
+    auto kpos_tile = [&](int buf) { return reinterpret_cast<int32_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 4); };
+    const uint32_t lds0 = lds_address(smem_raw);
 
     // consecutive workgroups take the same work rank of consecutive segments: the longest
     // items of every segment are dispatched first, and when S is a multiple of 8 a segment
@@ -104,29 +119,34 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = k_nomask / BN;            // leading tiles that need no mask
 
-    TileRegs<D, BN, THREADS> kt, vt;
-    const rsrc_t k_rsrc = make_rsrc(kbase, (uint32_t)k_count * D * 2);
-    const rsrc_t v_rsrc = make_rsrc(vbase, (uint32_t)k_count * D * 2);
-    const rsrc_t p_rsrc = make_rsrc(kib, (uint32_t)k_count * 4);
-    int kp_reg = 0, kp_row = 0;
-    auto fetch = [&](int jt) {
-        kt.load(k_rsrc, jt * kt.TILE_BYTES);
-        vt.load(v_rsrc, jt * vt.TILE_BYTES);
-        if (tid < BN) {
-            kp_reg = buffer_load4(p_rsrc, tid * 4, jt * BN * 4);
-            kp_row = jt * BN + tid;
-        }
+    AsyncTile<D, BN, THREADS> loader;
+    loader.init();
+    const u32x4 k_desc = make_desc(kbase, (uint32_t)k_count * D * 2);
+    const u32x4 v_desc = make_desc(vbase, (uint32_t)k_count * D * 2);
+    const u32x4 p_desc = make_desc(kib, (uint32_t)k_count * 4);
+    // every wavefront issues the same number of loads per tile (16 key positions each), so one
+    // vmcnt threshold serves all; tiles past the end read zeros into a buffer nobody uses
+    auto issue = [&](int jt, int buf) {
+        const uint32_t base = lds0 + (uint32_t)(buf * BUF_BYTES);
+        loader.load(k_desc, jt * loader.TILE_BYTES, base);
+        loader.load(v_desc, jt * loader.TILE_BYTES, base + TILE_ELEMS * 2);
+        if (lane < 16)
+            async_load4(p_desc, __builtin_amdgcn_readfirstlane(base + TILE_ELEMS * 4 + wave * 64), (wave * 16 + lane) * 4,
+                        jt * BN * 4);
     };
-    auto stash = [&](int buf) {
-        kt.template store<KST>(Ks[buf]);
-        vt.template store<VST>(Vs[buf]);
-        if (tid < BN) kpos_s[buf][tid] = kp_row < k_count ? kp_reg : INT32_MAX;   // keys past the end are never allowed
-    };
+
+    // lane-invariant offsets of the transposing V reads
+    int v_off[4][D / 32][2];
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4)
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db) swz_trans_offsets<D>(c4 * 16, db * 32, lane, v_off[c4][db][0], v_off[c4][db][1]);
 
     auto tile = [&](int buf, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint16_t* Kt = Ks[buf];
-        const uint16_t* Vt = Vs[buf];
+        const uint16_t* Kt = k_tile(buf);
+        const uint16_t* Vt = v_tile(buf);
+        const int32_t* kpos_t = kpos_tile(buf);
         // S^T = K Q^T - m : [key block kb][query block b]
         f32x16 sacc[2][QB];
 #pragma unroll
@@ -137,7 +157,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         for (int kk = 0; kk < D / 16; ++kk)
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                const f16x8 a = lds_rows<KST>(Kt, kb * 32 + l32, kk * 16 + h * 8);
+                const f16x8 a = swz_rows<D>(Kt, kb * 32 + l32, kk * 16 + h * 8);
 #pragma unroll
                 for (int b = 0; b < QB; ++b) sacc[kb][b] = mfma16(a, qf[b][kk], sacc[kb][b]);
             }
@@ -147,7 +167,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_s[buf][kb * 32 + 8 * g + 4 * h]);
+                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
 #pragma unroll
                     for (int b = 0; b < QB; ++b) {
                         if (kp.x > qpos[b]) sacc[kb][b][4 * g + 0] = -INFINITY;
@@ -226,30 +246,34 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         for (int c4 = 0; c4 < 4; ++c4)
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
-                const f16x8 a = lds_trans<VST>(Vt, c4 * 16, db * 32, lane);
+                const f16x8 a = swz_trans(Vt, v_off[c4][db][0], v_off[c4][db][1]);
 #pragma unroll
                 for (int b = 0; b < QB; ++b) oacc[b][db] = mfma16(a, pf[b][c4], oacc[b][db]);
             }
     };
 
-    if (n_tiles > 0) {
-        fetch(0);
-        stash(0);
-    }
-    __syncthreads();
-    // one step: prefetch the next tile into registers, compute on the current LDS buffer,
-    // park the prefetched tile in the other buffer (last read before the previous barrier)
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) issue(u, u);
+    // one step: wait for this wavefront's share of tile jt, mark keys past the end of a ragged
+    // tile (always a masked tile), barrier, refill the buffer everyone has just left, compute
+    int cur = 0;
     auto step = [&](int jt, auto masked_tag) {
-        const int buf = jt & 1;
-        const bool more = jt + 1 < n_tiles;
-        if (more) fetch(jt + 1);
-        tile(buf, masked_tag);
-        if (more) stash(buf ^ 1);
-        __syncthreads();
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        wait_async<LOADS_PER_TILE * (NBUF - 2)>();
+        if (MASKED && lane < 16) {
+            const int key = jt * BN + wave * 16 + lane;
+            if (key >= k_count) kpos_tile(cur)[wave * 16 + lane] = INT32_MAX;   // never allowed
+        }
+        lds_barrier();
+        const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
+        issue(jt + NBUF - 1, refill);
+        tile(cur, masked_tag);
+        cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;
     for (; jt < n_free; ++jt) step(jt, std::false_type{});
     for (; jt < n_tiles; ++jt) step(jt, std::true_type{});
+    wait_async<0>();   // nothing may still be landing in LDS when the wavefront ends
 
 #pragma unroll
     for (int b = 0; b < QB; ++b) {
@@ -280,7 +304,7 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const int32
                         const int32_t* work, int n_work, int S, int T, float tau, void* o, float* lse,
                         float* o_f32, hipStream_t st)
 {
-    constexpr size_t smem = 2 * FWD_TILE_N * ((D + 8) + (D + 16)) * 2 + 2 * FWD_TILE_N * 4;
+    constexpr size_t smem = (size_t)FwdRing<D>::NBUF * FwdRing<D>::BUF_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_f16_kernel<D, NW, QB>),

@@ -187,6 +187,92 @@ __device__ __forceinline__ f16x8 swz_trans(const uint16_t* tile, int off_a, int 
     return as_f16x8(make_uint4(a.x, a.y, b.x, b.y));
 }
 
+// ---------------------------------------------------------------------------
+// Asynchronous tile copies: buffer loads that write straight into LDS (no registers, no
+// LDS store instruction).  Lane i of a wavefront's load lands at lds_addr + 16 i, so a
+// 64-lane instruction fills 1 KiB of contiguous LDS; the swizzled tile layout is obtained by
+// choosing WHICH 16-byte chunk of the global tile each lane fetches.  The loads are issued
+// from inline assembly: the compiler then neither counts them nor forces them to complete
+// before later LDS reads, and the kernels place the s_waitcnt vmcnt(N) themselves (they are
+// the only vector-memory loads in flight inside the tile loops).  Rows past the end of the
+// descriptor's range land as zeros.
+typedef __attribute__((address_space(3))) unsigned char* lds_byte_ptr;
+
+__device__ __forceinline__ uint32_t lds_address(const void* p)   // byte address inside the workgroup's LDS
+{
+    return (uint32_t)(uintptr_t)(lds_byte_ptr)(const_cast<void*>(p));
+}
+
+// raw buffer descriptor (stride 0, range `bytes`) in scalar registers
+__device__ __forceinline__ u32x4 make_desc(const void* base, uint32_t bytes)
+{
+    const uint64_t a = (uint64_t)(uintptr_t)base;
+    u32x4 d;
+    d[0] = __builtin_amdgcn_readfirstlane((uint32_t)a);
+    d[1] = __builtin_amdgcn_readfirstlane((uint32_t)(a >> 32) & 0xffffu);
+    d[2] = __builtin_amdgcn_readfirstlane(bytes);
+    d[3] = 0x00020000u;
+    return d;
+}
+
+// lds_addr and soffset must be wave-uniform.  M0 carries the LDS address of the load; the
+// compiler flags it as a reserved register in the clobber list, which is the intent here.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ __forceinline__ void async_load16(u32x4 desc, uint32_t lds_addr, int voffset, int soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voffset), "s"(desc), "s"(soffset) : "memory", "m0");
+}
+__device__ __forceinline__ void async_load4(u32x4 desc, uint32_t lds_addr, int voffset, int soffset)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dword %1, %2, %3 offen lds"
+                 :: "s"(lds_addr), "v"(voffset), "s"(desc), "s"(soffset) : "memory", "m0");
+}
+#pragma clang diagnostic pop
+template <int N>
+__device__ __forceinline__ void wait_async()   // at most N asynchronous loads of this wavefront still in flight
+{
+    asm volatile("s_waitcnt vmcnt(%0)" :: "n"(N) : "memory");
+}
+// every LDS operation of this wavefront done, then the workgroup barrier (no memory fence:
+// a fence would make the compiler wait for ALL vector-memory traffic)
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+}
+
+// ROWS contiguous rows x D fp16 of global memory -> swizzled LDS tile (row stride D), by a
+// workgroup of THREADS lanes: ROUNDS loads per wavefront.
+template <int D, int ROWS, int THREADS>
+struct AsyncTile {
+    static constexpr int CH = D / 8;                      // 16-byte chunks per row
+    static constexpr int ROUNDS = ROWS * CH / THREADS;
+    static constexpr int TILE_BYTES = ROWS * D * 2;
+    static_assert(ROWS * CH % THREADS == 0, "tile must split evenly over the workgroup");
+    int voff[ROUNDS];
+
+    __device__ __forceinline__ void init()
+    {
+#pragma unroll
+        for (int u = 0; u < ROUNDS; ++u) {
+            const int pos = u * THREADS + (int)threadIdx.x;   // LDS chunk position this lane fills
+            const int row = pos / CH, slot = pos % CH;
+            voff[u] = (row * CH + (slot ^ swz<D>(row))) * 16;  // the chunk that belongs there
+        }
+    }
+    // tile_lds: LDS byte address of the tile; tile_byte_offset: wave-uniform offset into the buffer
+    __device__ __forceinline__ void load(u32x4 desc, int tile_byte_offset, uint32_t tile_lds) const
+    {
+        const uint32_t wave_base = tile_lds + ((uint32_t)threadIdx.x >> 6) * 1024u;
+#pragma unroll
+        for (int u = 0; u < ROUNDS; ++u)
+            async_load16(desc, __builtin_amdgcn_readfirstlane(wave_base + (uint32_t)(u * THREADS * 16)), voff[u],
+                         tile_byte_offset);
+    }
+};
+
 // Cooperative copy of ROWS contiguous rows x D fp16 (one tile) from global memory into
 // registers and on into an LDS tile.  Rows past the end of the resource read as zeros.
 template <int D, int ROWS, int THREADS>
