@@ -27,7 +27,11 @@
  *     need not clear them.
  *   - Every function returns SCFA_OK or a negative error code; nothing is
  *     launched when an argument check fails.  No function throws or aborts.
- *   - `flags` is reserved and must be 0.
+ *   - `flags`: 0, or SCFA_FLAG_STRICT_CAUSAL: a query attends keys at STRICTLY earlier
+ *     positions only (App. B.1: ">=" replaced by ">", the form used with shared
+ *     query / key projections).  The same flag must be given to scfa_block_ranges and to
+ *     the attention calls that consume its work lists.  The first token of every bucket
+ *     (or the first kept token) then has no allowed key: zero output row, LSE = -inf.
  */
 #ifndef SCFA_H
 #define SCFA_H
@@ -51,6 +55,8 @@ extern "C" {
 
 #define SCFA_HASH   0
 #define SCFA_QKDROP 1
+
+#define SCFA_FLAG_STRICT_CAUSAL 1   /* allowed keys are at strictly earlier positions */
 
 #define SCFA_MAX_BUCKETS 256
 #define SCFA_WORK_STRIDE 8      /* int32 words per work item */

@@ -20,6 +20,7 @@ SCFA_OK = 0
 SCFA_EINVAL, SCFA_EUNSUPPORTED, SCFA_EWORKSPACE, SCFA_EHIP = -1, -2, -3, -4
 SCFA_BF16, SCFA_F32, SCFA_F16 = 0, 1, 2
 SCFA_HASH, SCFA_QKDROP = 0, 1
+SCFA_FLAG_STRICT_CAUSAL = 1
 SCFA_WORK_STRIDE = 8
 KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_prep": 5,
               "bwd_dkdv": 6, "bwd_dq": 7, "fill": 8}
@@ -205,7 +206,7 @@ def scfa_gather_rows(x: torch.Tensor, idx: torch.Tensor, count=None, out=None, t
     return out
 
 
-def scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles, want_bwd=True, want_counters=True):
+def scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles, want_bwd=True, want_counters=True, flags=0):
     """-> fwd_work [S,n_fwd,8], bwd_work [S,n_bwd,8] or None, counters [S,4] int64 or None."""
     S, T = q_idx.shape
     fm, fn, bn, bm = tiles
@@ -216,33 +217,33 @@ def scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles, want_bwd=T
     bwd = torch.empty((S, n_bwd, SCFA_WORK_STRIDE), dtype=torch.int32, device=dev) if want_bwd else None
     cnt = torch.empty((S, 4), dtype=torch.int64, device=dev) if want_counters else None
     _check(lib().scfa_block_ranges(variant, _ptr(q_idx), _ptr(k_idx), _ptr(q_off), _ptr(k_off), S, T, nb,
-                                   fm, fn, bn, bm, 0, _ptr(fwd), _ptr(bwd), _ptr(cnt), _stream()),
+                                   fm, fn, bn, bm, int(flags), _ptr(fwd), _ptr(bwd), _ptr(cnt), _stream()),
            "scfa_block_ranges")
     return fwd, bwd, cnt
 
 
 def scfa_hash_attn_fwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, B, H, sm_scale, o_out=None, lse_out=None,
-                       o_f32_out=None):
+                       o_f32_out=None, flags=0):
     S, T, d = q_perm.shape
     assert S == B * H
     o = torch.empty((B, H, T, d), dtype=_out_dtype(q_perm), device=q_perm.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_perm.device) if lse_out is None else lse_out
     _check(lib().scfa_hash_attn_fwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
                                     _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_perm),
-                                    float(sm_scale), 0, _ptr(o), _ptr(lse), _ptr(o_f32_out), _stream()),
+                                    float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f32_out), _stream()),
            "scfa_hash_attn_fwd")
     return o, lse
 
 
 def scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_out=None, lse_out=None,
-                         o_f32_out=None):
+                         o_f32_out=None, flags=0):
     S, T, d = q_c.shape
     assert S == B * H
     o = torch.empty((B, H, T, d), dtype=_out_dtype(q_c), device=q_c.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_c.device) if lse_out is None else lse_out
     _check(lib().scfa_qkdrop_attn_fwd(_ptr(q_c), _ptr(k_c), _ptr(v_c), _ptr(q_idx), _ptr(k_idx), _ptr(n_q),
                                       _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_c),
-                                      float(sm_scale), 0, _ptr(o), _ptr(lse), _ptr(o_f32_out), _stream()),
+                                      float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f32_out), _stream()),
            "scfa_qkdrop_attn_fwd")
     return o, lse
 
@@ -258,7 +259,7 @@ def _bwd_outputs(B, H, T, d, dev, outs):
 
 
 def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, bwd_work, o, lse, d_o, B, H, sm_scale,
-                       ws=None, outs=None, o_f32=None):
+                       ws=None, outs=None, o_f32=None, flags=0):
     S, T, d = q_perm.shape
     dt = dtype_code(q_perm)
     need = scfa_attn_bwd_workspace_bytes(S, T, d, dt)
@@ -267,14 +268,14 @@ def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, bwd_work,
     dq, dk, dv = _bwd_outputs(B, H, T, d, q_perm.device, outs)
     _check(lib().scfa_hash_attn_bwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
                                     _ptr(fwd_work), fwd_work.shape[1], _ptr(bwd_work), bwd_work.shape[1],
-                                    _ptr(o), _ptr(o_f32), _ptr(lse), _ptr(d_o), B, H, T, d, dt, float(sm_scale), 0,
-                                    _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()),
+                                    _ptr(o), _ptr(o_f32), _ptr(lse), _ptr(d_o), B, H, T, d, dt, float(sm_scale),
+                                    int(flags), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()),
            "scfa_hash_attn_bwd")
     return dq, dk, dv
 
 
 def scfa_qkdrop_attn_bwd(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work, o, lse, d_o, B, H, sm_scale,
-                         ws=None, outs=None, o_f32=None):
+                         ws=None, outs=None, o_f32=None, flags=0):
     S, T, d = q_c.shape
     dt = dtype_code(q_c)
     need = scfa_attn_bwd_workspace_bytes(S, T, d, dt)
@@ -284,7 +285,7 @@ def scfa_qkdrop_attn_bwd(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_wo
     _check(lib().scfa_qkdrop_attn_bwd(_ptr(q_c), _ptr(k_c), _ptr(v_c), _ptr(q_idx), _ptr(k_idx), _ptr(n_q),
                                       _ptr(n_k), _ptr(fwd_work), fwd_work.shape[1], _ptr(bwd_work),
                                       bwd_work.shape[1], _ptr(o), _ptr(o_f32), _ptr(lse), _ptr(d_o), B, H, T, d, dt,
-                                      float(sm_scale), 0, _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
+                                      float(sm_scale), int(flags), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
                                       _stream()), "scfa_qkdrop_attn_bwd")
     return dq, dk, dv
 

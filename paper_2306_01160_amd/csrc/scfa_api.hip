@@ -63,7 +63,7 @@ static int check_attn_common(const void* q, const void* k, const void* v, const 
     if (B <= 0 || H <= 0 || T <= 0 || n_work <= 0) return SCFA_EINVAL;
     if (!(sm_scale > 0.f) || !isfinite(sm_scale)) return SCFA_EINVAL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return SCFA_EINVAL;
-    if (flags != 0) return SCFA_EUNSUPPORTED;
+    if ((flags & ~SCFA_FLAG_STRICT_CAUSAL) != 0) return SCFA_EUNSUPPORTED;
     if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
     if (d != 64 && d != 128) return SCFA_EUNSUPPORTED;
     if ((long long)B * H * (long long)n_work > 0x7fffffffLL) return SCFA_EUNSUPPORTED;
@@ -89,8 +89,9 @@ static int attn_fwd_impl(const void* q, const void* k, const void* v, const int3
     }
     if (dtype == SCFA_F32)
         return launch_attn_fwd_f32((const float*)q, (const float*)k, (const float*)v, q_idx, k_idx, work,
-                                   n_work, S, T, d, sm_scale, (float*)o, lse, st);
-    return launch_attn_fwd_bf16(q, k, v, q_idx, k_idx, work, n_work, S, T, d, sm_scale, o, lse, o_f32, st);
+                                   n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, (float*)o, lse, st);
+    return launch_attn_fwd_bf16(q, k, v, q_idx, k_idx, work, n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, o,
+                                lse, o_f32, st);
 }
 
 static int attn_bwd_impl(const void* q, const void* k, const void* v, const int32_t* q_idx,
@@ -133,10 +134,10 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
     rc = launch_bwd_prep_bf16(o, o_f32, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
     rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, d,
-                                   dk, dv, st);
+                                   flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
     if (rc != SCFA_OK) return rc;
     return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd,
-                                   S, T, d, sm_scale, dq, st);
+                                   S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dq, st);
 }
 
 }  // namespace scfa
@@ -268,7 +269,7 @@ int scfa_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx, c
     if (!q_idx || !k_idx || !q_off || !k_off || !fwd_work_out || S <= 0 || T <= 0 || nb <= 0) return SCFA_EINVAL;
     if (variant != SCFA_HASH && variant != SCFA_QKDROP) return SCFA_EINVAL;
     if (variant == SCFA_QKDROP && nb != 1) return SCFA_EINVAL;
-    if (flags != 0) return SCFA_EUNSUPPORTED;
+    if ((flags & ~SCFA_FLAG_STRICT_CAUSAL) != 0) return SCFA_EUNSUPPORTED;
     if (nb > SCFA_MAX_BUCKETS) return SCFA_EUNSUPPORTED;
     const bool fwd_ok = (fwd_tile_m == FWD_TILE_M && fwd_tile_n == FWD_TILE_N) ||
                         (fwd_tile_m == F32_TILE_M && fwd_tile_n == F32_TILE_N);
@@ -277,7 +278,7 @@ int scfa_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx, c
     const int n_bwd = scfa_num_work_items(T, nb, bwd_tile_n);
     if (n_fwd > 8192 || n_bwd > 8192) return SCFA_EUNSUPPORTED;   // ranking scratch lives in LDS
     return launch_block_ranges(variant, q_idx, k_idx, q_off, k_off, S, T, nb, fwd_tile_m, fwd_tile_n, bwd_tile_n,
-                               bwd_tile_m, n_fwd, n_bwd, fwd_work_out, bwd_work_out, counters_out,
+                               bwd_tile_m, n_fwd, n_bwd, flags & SCFA_FLAG_STRICT_CAUSAL, fwd_work_out, bwd_work_out, counters_out,
                                (hipStream_t)stream);
 }
 

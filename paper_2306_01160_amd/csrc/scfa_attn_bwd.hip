@@ -226,7 +226,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const uint16_t* __restrict__ do_perm, const uint16_t* __restrict__ aux_perm,
     const float* __restrict__ inv_scale,
     const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
-    const int32_t* __restrict__ work, int n_work, int S, int T,
+    const int32_t* __restrict__ work, int n_work, int S, int T, int strict,
     float* __restrict__ dk, float* __restrict__ dv)
 {
     constexpr int BM = BWD_TILE_M;
@@ -247,6 +247,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const int kr = min(krow, k_count - 1);            // keys past the end repeat the last one; never written
     const int kpos_ld = k_idx[seg + k_begin + kr];
     const int kpos = kvalid ? kpos_ld : INT32_MAX;
+    const int kcmp = kvalid ? kpos_ld + strict : INT32_MAX;   // a query is allowed iff its position >= kcmp
 
     f16x8 kf[D / 16], vf[D / 16];
     {
@@ -337,7 +338,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(sacc[qb][4 * g + e]);
-                    if (MASKED) { if (kpos > qpa[e]) p = 0.f; }     // causal test on original positions
+                    if (MASKED) { if (kcmp > qpa[e]) p = 0.f; }     // causal test on original positions
                     sacc[qb][4 * g + e] = p;
                     pacc[qb][4 * g + e] = p * pacc[qb][4 * g + e];
                 }
@@ -395,7 +396,7 @@ template <int D>
 static int launch_dkdv_t(const void* q, const void* k, const void* v, const void* do_perm,
                          const void* aux_perm, const float* inv_scale,
                          const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S,
-                         int T, float* dk, float* dv, hipStream_t st)
+                         int T, int strict, float* dk, float* dv, hipStream_t st)
 {
     const size_t smem = sizeof(DkdvSmem<D>);
     static bool attr_set = false;
@@ -407,7 +408,7 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_idx, k_idx,
-                       work, n_work, S, T, dk, dv);
+                       work, n_work, S, T, strict, dk, dv);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -415,13 +416,13 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
                               const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, float* dk, float* dv, hipStream_t st)
+                              int S, int T, int d, int strict, float* dk, float* dv, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DKDV, st);
     if (d == 64)
-        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, dk, dv, st);
+        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, strict, dk, dv, st);
     if (d == 128)
-        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, dk, dv, st);
+        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, strict, dk, dv, st);
     return SCFA_EUNSUPPORTED;
 }
 
@@ -445,7 +446,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
     const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
     const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
-    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, float* __restrict__ dq)
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict, float* __restrict__ dq)
 {
     constexpr int BN = FWD_TILE_N;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -465,6 +466,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     const int qr = min(qrow, q_count - 1);              // rows past the end repeat the last one; never written
     const int qpos_ld = q_idx[seg + q_begin + qr];
     const int qpos = qvalid ? qpos_ld : -1;
+    const int qcmp = qvalid ? qpos_ld - strict : -1;   // a key is allowed iff its position <= qcmp
     const float lse_ld = lse_perm[seg + q_begin + qr];
     const float lse2 = (qvalid && lse_ld != -INFINITY) ? fmaf(lse_ld, LOG2E, -RTZ_BIAS_LOG2) : INFINITY;
     const float delta = delta_perm[seg + q_begin + qr];
@@ -537,7 +539,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(sacc[kb][4 * g + e]);
-                    if (MASKED) { if (kpa[e] > qpos) p = 0.f; }     // causal test on original positions
+                    if (MASKED) { if (kpa[e] > qcmp) p = 0.f; }     // causal test on original positions
                     pacc[kb][4 * g + e] = p * pacc[kb][4 * g + e];
                 }
             }
@@ -587,7 +589,7 @@ template <int D>
 static int launch_dq_t(const void* q, const void* k, const void* v, const void* do_perm,
                        const float* lse_perm, const float* delta_perm, const float* inv_scale,
                        const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S, int T,
-                       float tau, float* dq, hipStream_t st)
+                       float tau, int strict, float* dq, hipStream_t st)
 {
     const size_t smem = sizeof(DqSmem<D>);
     static bool attr_set = false;
@@ -599,7 +601,7 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dq_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx,
-                       work, n_work, S, T, tau, dq);
+                       work, n_work, S, T, tau, strict, dq);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -607,13 +609,13 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
                             const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,
-                            int S, int T, int d, float tau, float* dq, hipStream_t st)
+                            int S, int T, int d, float tau, int strict, float* dq, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DQ, st);
     if (d == 64)
-        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, dq, st);
+        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, strict, dq, st);
     if (d == 128)
-        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, dq, st);
+        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, strict, dq, st);
     return SCFA_EUNSUPPORTED;
 }
 

@@ -15,7 +15,7 @@ template <int D>
 __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
     const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
-    const int32_t* __restrict__ work, int n_work, int T, float tau, float* __restrict__ o,
+    const int32_t* __restrict__ work, int n_work, int T, float tau, int strict, float* __restrict__ o,
     float* __restrict__ lse)
 {
     __shared__ float Ks[F32_TILE_N][D];
@@ -63,7 +63,7 @@ __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
                                                               : INT32_MAX;
         __syncthreads();
         for (int j = 0; j < F32_TILE_N; ++j) {
-            if (kpos[j] > qpos) continue;   // causal test on original positions
+            if (kpos[j] > qpos - strict) continue;   // causal test on original positions (strict: key must be earlier)
             float sc = 0.f;
 #pragma unroll
             for (int c = 0; c < D; ++c) sc = fmaf(qr[c], Ks[j][c], sc);
@@ -88,14 +88,14 @@ __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
 
 int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const int32_t* q_idx,
                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
-                        float tau, float* o, float* lse, hipStream_t st)
+                        float tau, int strict, float* o, float* lse, hipStream_t st)
 {
     dim3 grid(n_work, S), block(F32_TILE_M);
     ProfScope prof(SCFA_K_FWD, st);
     if (d == 64)
-        hipLaunchKernelGGL(attn_fwd_f32_kernel<64>, grid, block, 0, st, q, k, v, q_idx, k_idx, work, n_work, T, tau, o, lse);
+        hipLaunchKernelGGL(attn_fwd_f32_kernel<64>, grid, block, 0, st, q, k, v, q_idx, k_idx, work, n_work, T, tau, strict, o, lse);
     else if (d == 128)
-        hipLaunchKernelGGL(attn_fwd_f32_kernel<128>, grid, block, 0, st, q, k, v, q_idx, k_idx, work, n_work, T, tau, o, lse);
+        hipLaunchKernelGGL(attn_fwd_f32_kernel<128>, grid, block, 0, st, q, k, v, q_idx, k_idx, work, n_work, T, tau, strict, o, lse);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());

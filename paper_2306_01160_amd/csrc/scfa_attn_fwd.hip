@@ -52,7 +52,7 @@ template <int D, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
-    const int32_t* __restrict__ work, int n_work, int S, int T, float tau,
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
     uint16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ o_f32)
 {
     static_assert(NW * QB * 32 == FWD_TILE_M, "workgroup must cover the forward query tile");
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
 
-    int qrow[QB], qpos[QB];
+    int qrow[QB], qpos[QB], qcmp[QB];   // qcmp: a key is allowed iff its position <= qcmp
     bool qvalid[QB];
     f16x8 qf[QB][D / 16];
 #pragma unroll
@@ -91,7 +91,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         qvalid[b] = qrow[b] < q_count;
         const int qr = min(qrow[b], q_count - 1);          // rows past the end repeat the last one
         const int qp_ = q_idx[seg + q_begin + qr];
-        qpos[b] = qvalid[b] ? qp_ : -1;                    // position -1: every key is masked
+        qpos[b] = qvalid[b] ? qp_ : -1;
+        qcmp[b] = qvalid[b] ? qp_ - strict : -1;           // -1: every key is masked
         const uint16_t* qp = q + (seg + q_begin + qr) * D + h * 8;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) qf[b][kk] = as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16));
@@ -170,10 +171,10 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                     const int4 kp = *reinterpret_cast<const int4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
 #pragma unroll
                     for (int b = 0; b < QB; ++b) {
-                        if (kp.x > qpos[b]) sacc[kb][b][4 * g + 0] = -INFINITY;
-                        if (kp.y > qpos[b]) sacc[kb][b][4 * g + 1] = -INFINITY;
-                        if (kp.z > qpos[b]) sacc[kb][b][4 * g + 2] = -INFINITY;
-                        if (kp.w > qpos[b]) sacc[kb][b][4 * g + 3] = -INFINITY;
+                        if (kp.x > qcmp[b]) sacc[kb][b][4 * g + 0] = -INFINITY;
+                        if (kp.y > qcmp[b]) sacc[kb][b][4 * g + 1] = -INFINITY;
+                        if (kp.z > qcmp[b]) sacc[kb][b][4 * g + 2] = -INFINITY;
+                        if (kp.w > qcmp[b]) sacc[kb][b][4 * g + 3] = -INFINITY;
                     }
                 }
         }
@@ -301,8 +302,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
 
 template <int D, int NW, int QB>
 static int launch_fwd_t(const void* q, const void* k, const void* v, const int32_t* q_idx, const int32_t* k_idx,
-                        const int32_t* work, int n_work, int S, int T, float tau, void* o, float* lse,
-                        float* o_f32, hipStream_t st)
+                        const int32_t* work, int n_work, int S, int T, float tau, int strict, void* o,
+                        float* lse, float* o_f32, hipStream_t st)
 {
     constexpr size_t smem = (size_t)FwdRing<D>::NBUF * FwdRing<D>::BUF_BYTES;
     static bool attr_set = false;
@@ -314,18 +315,18 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const int32
     dim3 grid((unsigned)((size_t)S * n_work));
     hipLaunchKernelGGL((attn_fwd_f16_kernel<D, NW, QB>), grid, dim3(NW * 64), smem, st, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, q_idx, k_idx, work, n_work, S, T, tau,
-                       (uint16_t*)o, lse, o_f32);
+                       strict, (uint16_t*)o, lse, o_f32);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
 int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
-                         float tau, void* o, float* lse, float* o_f32, hipStream_t st)
+                         float tau, int strict, void* o, float* lse, float* o_f32, hipStream_t st)
 {
     ProfScope prof(SCFA_K_FWD, st);
-    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
-    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, o, lse, o_f32, st);
+    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f32, st);
+    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f32, st);
     return SCFA_EUNSUPPORTED;
 }
 

@@ -58,26 +58,26 @@ int launch_gather_rows(int n_tensors, const void* const* x, const int32_t* const
                        const float* scale, void* const* out, int S, int T, int row_bytes, int mode, hipStream_t st);
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
-                        int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
+                        int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int strict,
                         int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st);
 int launch_zero_rows(const int32_t* idx, const int32_t* count, int S, int T, int row_bytes,
                      void* out0, void* out1, float* vec, float vec_value, hipStream_t st);
 int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const int32_t* q_idx,
                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
-                        float tau, float* o, float* lse, hipStream_t st);
+                        float tau, int strict, float* o, float* lse, hipStream_t st);
 int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
-                         float tau, void* o, float* lse, float* o_f32, hipStream_t st);
+                         float tau, int strict, void* o, float* lse, float* o_f32, hipStream_t st);
 int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st);
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
                               const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, float* dk, float* dv, hipStream_t st);
+                              int S, int T, int d, int strict, float* dk, float* dv, hipStream_t st);
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
                             const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,
-                            int S, int T, int d, float tau, float* dq, hipStream_t st);
+                            int S, int T, int d, float tau, int strict, float* dq, hipStream_t st);
 
 }  // namespace scfa

@@ -51,7 +51,9 @@ struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket; };
 // "b" the ranged side.
 //   FORWARD : b range = keys with pos <= max a pos;  extra = #keys with pos <= min a pos
 //   BACKWARD: b range = queries with pos >= min a pos; extra = #queries of the range with pos < max a pos
-template <bool FORWARD>
+// STRICT (a key is visible only to later positions, App. B.1's ">" in place of ">="): the
+// comparisons with equality swap sides, <= becomes < and >= becomes >.
+template <bool FORWARD, bool STRICT>
 __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_idx,
                            const int32_t* a_off, const int32_t* b_off, int nb, int tile_a,
                            int tile_b, int n_items_max, int32_t* __restrict__ work_out,
@@ -86,13 +88,14 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_i
         const int bb = b_off[b], bn = b_off[b + 1] - b_off[b];
         if (FORWARD) {
             it.b_begin = bb;
-            it.b_count = count_le(b_idx + bb, bn, pos_max);
-            it.b_extra = count_le(b_idx + bb, bn, pos_min);
+            it.b_count = STRICT ? count_lt(b_idx + bb, bn, pos_max) : count_le(b_idx + bb, bn, pos_max);
+            it.b_extra = STRICT ? count_lt(b_idx + bb, bn, pos_min) : count_le(b_idx + bb, bn, pos_min);
         } else {
-            const int first = count_lt(b_idx + bb, bn, pos_min);
+            const int first = STRICT ? count_le(b_idx + bb, bn, pos_min) : count_lt(b_idx + bb, bn, pos_min);
             it.b_begin = bb + first;
             it.b_count = bn - first;
-            it.b_extra = count_lt(b_idx + bb, bn, pos_max) - first;
+            it.b_extra = (STRICT ? count_le(b_idx + bb, bn, pos_max) : count_lt(b_idx + bb, bn, pos_max)) - first;
+            if (it.b_extra < 0) it.b_extra = 0;
         }
         return it;
     };
@@ -140,7 +143,7 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_i
 __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int variant, const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
     const int32_t* __restrict__ q_off_g, const int32_t* __restrict__ k_off_g, int T, int nb,
-    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int stage_in_lds,
+    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int stage_in_lds, int strict,
     int32_t* __restrict__ fwd_work, int32_t* __restrict__ bwd_work, long long* __restrict__ counters)
 {
     extern __shared__ int32_t smem[];
@@ -190,20 +193,22 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     }
     __syncthreads();
     long long* cnt = counters ? counters + (size_t)s * 4 : nullptr;
+    int32_t* fw = fwd_work + (size_t)s * n_fwd * WORK_STRIDE;
+    int32_t* bw = bwd_work ? bwd_work + (size_t)s * n_bwd * WORK_STRIDE : nullptr;
     if (!backward) {
-        build_list<true>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd,
-                         fwd_work + (size_t)s * n_fwd * WORK_STRIDE, cnt, s_tile_base, s_cost);
+        if (strict) build_list<true, true>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd, fw, cnt, s_tile_base, s_cost);
+        else build_list<true, false>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd, fw, cnt, s_tile_base, s_cost);
         if (!bwd_work && cnt && threadIdx.x == 0) { cnt[2] = 0; cnt[3] = 0; }
     } else {
-        build_list<false>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd,
-                          bwd_work + (size_t)s * n_bwd * WORK_STRIDE, cnt ? cnt + 2 : nullptr,
-                          s_tile_base, s_cost);
+        long long* c2 = cnt ? cnt + 2 : nullptr;
+        if (strict) build_list<false, true>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd, bw, c2, s_tile_base, s_cost);
+        else build_list<false, false>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd, bw, c2, s_tile_base, s_cost);
     }
 }
 
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         const int32_t* q_off, const int32_t* k_off, int S, int T, int nb,
-                        int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd,
+                        int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int strict,
                         int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st)
 {
     const int n_max = n_fwd > n_bwd ? n_fwd : n_bwd;
@@ -218,7 +223,7 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
     }
     ProfScope prof(SCFA_K_RANGES, st);
     hipLaunchKernelGGL(block_ranges_kernel, dim3(S, bwd_work ? 2 : 1), dim3(RANGES_THREADS), smem, st, variant, q_idx,
-                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, stage, fwd_work,
+                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, stage, strict, fwd_work,
                        bwd_work, (long long*)counters);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;

@@ -21,6 +21,7 @@ class Context:
     H: int
     nb: int
     sm_scale: float
+    flags: int
     q_p: torch.Tensor
     k_p: torch.Tensor
     v_p: torch.Tensor
@@ -52,19 +53,20 @@ def _o_f32_buffer(q, need_bwd):
     return torch.empty(q.shape, dtype=torch.float32, device=q.device)
 
 
-def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
+def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True, strict=False):
     """Hash-sparse attention forward (Sec. 3.2).  Returns (O, LSE, ctx)."""
     B, H, T, d = q.shape
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
+    flags = sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0
     (q_idx, q_bs, q_off), (k_idx, k_bs, k_off) = sc.scfa_sort_by_bucket_pair(_seg(bucket_q), _seg(bucket_k), nb,
                                                                              want_sorted=False)
     q_p, k_p, v_p = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, to_f16=q.dtype == torch.bfloat16,
                                        q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
-                                                        want_bwd=need_bwd)
+                                                        want_bwd=need_bwd, flags=flags)
     o_f32 = _o_f32_buffer(q, need_bwd)
-    o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f32_out=o_f32)
-    ctx = Context(sc.SCFA_HASH, B, H, nb, sm_scale, q_p, k_p, v_p, q_idx, k_idx, None, None, fwd_work, bwd_work,
+    o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f32_out=o_f32, flags=flags)
+    ctx = Context(sc.SCFA_HASH, B, H, nb, sm_scale, flags, q_p, k_p, v_p, q_idx, k_idx, None, None, fwd_work, bwd_work,
                   counters, o, lse, o_f32, q_bs, k_bs, q_off, k_off)
     return o, lse, ctx
 
@@ -72,21 +74,22 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True):
 def hash_backward(ctx: Context, d_o, ws=None, outs=None):
     """dQ, dK, dV (fp32, original order) of hash-sparse attention."""
     return sc.scfa_hash_attn_bwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_idx, ctx.k_idx, ctx.fwd_work, ctx.bwd_work,
-                                 ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale, ws=ws, outs=outs, o_f32=ctx.o_f32)
+                                 ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale, ws=ws, outs=outs, o_f32=ctx.o_f32, flags=ctx.flags)
 
 
-def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True):
+def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True, strict=False):
     """QK-sparse attention forward (Sec. 3.1).  Returns (O, LSE, ctx)."""
     B, H, T, d = q.shape
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
+    flags = sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0
     (q_idx, n_q), (k_idx, n_k) = sc.scfa_compact_keep_pair(_seg(keep_q), _seg(keep_k))
     q_c, k_c, v_c = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, n_q, n_k,
                                        to_f16=q.dtype == torch.bfloat16, q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_QKDROP, q_idx, k_idx, n_q, n_k, 1, tiles,
-                                                        want_bwd=need_bwd)
+                                                        want_bwd=need_bwd, flags=flags)
     o_f32 = _o_f32_buffer(q, need_bwd)
-    o, lse = sc.scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_f32_out=o_f32)
-    ctx = Context(sc.SCFA_QKDROP, B, H, 1, sm_scale, q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work,
+    o, lse = sc.scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_f32_out=o_f32, flags=flags)
+    ctx = Context(sc.SCFA_QKDROP, B, H, 1, sm_scale, flags, q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work,
                   counters, o, lse, o_f32)
     return o, lse, ctx
 
@@ -94,4 +97,4 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True):
 def qkdrop_backward(ctx: Context, d_o, ws=None, outs=None):
     return sc.scfa_qkdrop_attn_bwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_idx, ctx.k_idx, ctx.n_q, ctx.n_k,
                                    ctx.fwd_work, ctx.bwd_work, ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale,
-                                   ws=ws, outs=outs, o_f32=ctx.o_f32)
+                                   ws=ws, outs=outs, o_f32=ctx.o_f32, flags=ctx.flags)

@@ -23,13 +23,19 @@ def to_gpu(wl):
     return q, k, v, do, lq, lk
 
 
+def is_strict(wl):
+    """workloads tagged meta['strict'] use the strictly-causal mask (keys at earlier positions only)"""
+    return bool(wl.meta.get("strict", False))
+
+
 def run_gpu(wl, backward=True):
     q, k, v, do, lq, lk = to_gpu(wl)
+    strict = is_strict(wl)
     if wl.variant == workloads.HASH:
-        o, lse, ctx = pipeline.hash_forward(q, k, v, lq, lk, wl.nb, wl.tau, need_bwd=backward)
+        o, lse, ctx = pipeline.hash_forward(q, k, v, lq, lk, wl.nb, wl.tau, need_bwd=backward, strict=strict)
         grads = pipeline.hash_backward(ctx, do) if backward else None
     else:
-        o, lse, ctx = pipeline.qkdrop_forward(q, k, v, lq, lk, wl.tau, need_bwd=backward)
+        o, lse, ctx = pipeline.qkdrop_forward(q, k, v, lq, lk, wl.tau, need_bwd=backward, strict=strict)
         grads = pipeline.qkdrop_backward(ctx, do) if backward else None
     torch.cuda.synchronize()
     return o, lse, grads, ctx
@@ -53,7 +59,8 @@ def compare_forward(wl, o, lse, segs=None, rows=None):
     segs = np.arange(S) if segs is None else np.asarray(segs)
     lq, lk = labels(wl)
     Q, K, V = (seg64(wl, a)[segs] for a in (wl.q, wl.k, wl.v))
-    O_ref, L_ref = oracle.attention_forward(Q, K, V, lq[segs], lk[segs], oracle_variant(wl), wl.tau, rows=rows)
+    O_ref, L_ref = oracle.attention_forward(Q, K, V, lq[segs], lk[segs], oracle_variant(wl), wl.tau,
+                                             strict=is_strict(wl), rows=rows)
     og = o.float().cpu().numpy().reshape(S, T, d)[segs]
     lg = lse.cpu().numpy().reshape(S, T)[segs]
     if rows is not None:
@@ -72,7 +79,7 @@ def compare_backward(wl, grads, segs=None, q_rows=None, k_rows=None):
     lq, lk = labels(wl)
     Q, K, V, dO = (seg64(wl, a)[segs] for a in (wl.q, wl.k, wl.v, wl.do))
     dQ_ref, dK_ref, dV_ref = oracle.attention_backward(Q, K, V, dO, lq[segs], lk[segs], oracle_variant(wl),
-                                                       wl.tau, q_rows=q_rows, k_rows=k_rows)
+                                                       wl.tau, strict=is_strict(wl), q_rows=q_rows, k_rows=k_rows)
     out = {}
     for name, g, ref, rows in (("dQ", grads[0], dQ_ref, q_rows), ("dK", grads[1], dK_ref, k_rows),
                                ("dV", grads[2], dV_ref, k_rows)):

@@ -53,7 +53,7 @@ def test_argument_checks_reject_before_any_launch():
     assert L.scfa_block_ranges(0, one, one, one, one, 1, 8, 2, 100, 64, 128, 64, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 48, 0, 0.125, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, -1.0, 0, one, one, None, None) == binding.SCFA_EINVAL
-    assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, 0.125, 1, one, one, None, None) == binding.SCFA_EUNSUPPORTED
+    assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, 0.125, 2, one, one, None, None) == binding.SCFA_EUNSUPPORTED   # unknown flag bit
     ws = ctypes.c_void_p(256)
     assert L.scfa_hash_attn_bwd(one, one, one, one, one, one, 1, one, 1, one, None, one, one, 1, 1, 8, 64, 0, 0.125, 0,
                                 one, one, one, ws, 16, None) == binding.SCFA_EWORKSPACE

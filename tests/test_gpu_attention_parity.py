@@ -54,6 +54,40 @@ def test_qkdrop_fp32_forward():
     _full_check(W.qkdrop_bernoulli(7, 1, 2, 300, 64, 0.5, 0.5, dtype="f32", passes="fwd"), backward=False)
 
 
+# --------------------------------------------------------------- strictly-causal mask
+
+def _strict(wl, shared_qk=False):
+    wl.meta["strict"] = True
+    if shared_qk:      # keys = queries and one set of labels (the paper's shared-projection setting)
+        wl.k = wl.q.copy()
+        wl.lab_k = wl.lab_q.copy()
+    return wl
+
+
+@pytest.mark.parametrize("T,nb,d,shared", [(700, 4, 64, False), (1500, 2, 128, False), (1029, 8, 64, True),
+                                           (130, 1, 64, True)])
+def test_strict_causal_hash_bf16(T, nb, d, shared):
+    """App. B.1's ">" mask: a token does not attend itself; the first query of each bucket is stranded."""
+    wl = _strict(W.hash_uniform(500 + T, 1, 2, T, d, nb), shared)
+    errs = _full_check(wl)
+    if shared:   # with shared labels the first token of every bucket has no earlier key
+        o, lse, _, _ = run_gpu(wl, backward=False)
+        lab = wl.lab_q.reshape(wl.S, wl.T)
+        for s in range(wl.S):
+            for b in np.unique(lab[s]):
+                first = int(np.flatnonzero(lab[s] == b)[0])
+                assert np.isneginf(lse.cpu().numpy().reshape(wl.S, wl.T)[s, first])
+
+
+@pytest.mark.parametrize("T,pq,pk,d", [(777, 0.5, 0.5, 64), (600, 1.0, 1.0, 128)])
+def test_strict_causal_qkdrop_bf16(T, pq, pk, d):
+    _full_check(_strict(W.qkdrop_bernoulli(600 + T, 1, 2, T, d, pq, pk)))
+
+
+def test_strict_causal_fp32_forward():
+    _full_check(_strict(W.hash_uniform(77, 1, 2, 300, 64, 3, dtype="f32", passes="fwd")), backward=False)
+
+
 # --------------------------------------------------------------- degenerate cases
 
 def test_bucket_present_in_q_but_absent_in_k_gives_zero_rows():

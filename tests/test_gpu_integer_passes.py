@@ -161,7 +161,7 @@ def test_pair_entry_points_match_single_calls(S, T, nb):
 
 # ------------------------------------------------------------------ schedule
 
-def _check_schedule(variant, lab_q, lab_k, nb, tiles):
+def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
     """Several schedules are correct; check what must hold: every allowed pair is covered
     exactly once, claimed mask-free regions are mask-free, ranges are tight, items are
     ordered by decreasing work, counters match the emitted items."""
@@ -179,11 +179,12 @@ def _check_schedule(variant, lab_q, lab_k, nb, tiles):
         rq, nq = oracle.compact_keep(lab_q); rk, nk = oracle.compact_keep(lab_k)
         ovar = oracle.QKDROP
     assert np.array_equal(q_idx.cpu().numpy(), rq) and np.array_equal(k_idx.cpu().numpy(), rk)
-    fwd, bwd, cnt = sc.scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles)
+    fwd, bwd, cnt = sc.scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles,
+                                         flags=sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0)
     torch.cuda.synchronize()
     fwd, bwd, cnt = fwd.cpu().numpy(), bwd.cpu().numpy(), cnt.cpu().numpy()
     for s in range(S):
-        M = oracle.allowed_mask(lab_q[s], lab_k[s], ovar)[np.ix_(rq[s], rk[s])]   # permuted coordinates
+        M = oracle.allowed_mask(lab_q[s], lab_k[s], ovar, strict=strict)[np.ix_(rq[s], rk[s])]   # permuted coordinates
         M[nq[s]:, :] = False; M[:, nk[s]:] = False
         # forward list
         covered = np.zeros(T, bool)
@@ -244,6 +245,20 @@ def test_schedule_qkdrop(S, T, pq, pk):
     kq = (rng.random((S, T)) < pq).astype(np.uint8)
     kk = (rng.random((S, T)) < pk).astype(np.uint8)
     _check_schedule(sc.SCFA_QKDROP, kq, kk, 1, sc.scfa_tile_config(64, sc.SCFA_BF16))
+
+
+@pytest.mark.parametrize("S,T,nb", [(2, 700, 4), (1, 129, 3), (1, 1024, 1)])
+def test_schedule_strict_causal(S, T, nb):
+    """Strictly-earlier keys only (App. B.1's ">"): same validity conditions against the strict mask,
+    for both variants; queries and keys share their labels in the second case (shared projections)."""
+    rng = np.random.default_rng(T * 3 + nb)
+    bq = rng.integers(0, nb, (S, T)).astype(np.int32)
+    bk = rng.integers(0, nb, (S, T)).astype(np.int32)
+    tiles = sc.scfa_tile_config(64, sc.SCFA_BF16)
+    _check_schedule(sc.SCFA_HASH, bq, bk, nb, tiles, strict=True)
+    _check_schedule(sc.SCFA_HASH, bq, bq, nb, tiles, strict=True)
+    kq = (rng.random((S, T)) < 0.5).astype(np.uint8)
+    _check_schedule(sc.SCFA_QKDROP, kq, kq, 1, tiles, strict=True)
 
 
 def test_schedule_regular_case_is_lower_triangular():
