@@ -2,6 +2,7 @@
 """Benchmark of the Sparse Causal Flash Attention hot path on ONE MI355X.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline] [--workload c4|c3]
+    python bench.py --sweep hash|qkdrop      (speed-up over dense causal against sparsity and T)
 
 A "step" is one pass of the whole hot path over one batch of synthetic input that is
 already resident in HBM: stable sort by bucket (queries, keys), row gather (Q, K, V),
@@ -69,21 +70,31 @@ def count_allowed_pairs(lab_q, lab_k, nb):
 
 
 class HashJob:
-    """Device-resident inputs of one hash-sparse workload and the step function."""
+    """Device-resident inputs of one workload (hash-sparse, or QK-dropping when nb is None) and
+    the step function: the whole hot path, forward and backward."""
 
-    def __init__(self, wl):
+    def __init__(self, wl=None, tensors=None, nb=None, tau=None):
         import torch
         from paper_2306_01160_amd import pipeline
         self.torch, self.pipeline, self.wl = torch, pipeline, wl
-        dev = torch.device("cuda:0")
-        self.q, self.k, self.v, self.do = (torch.from_numpy(a).to(dev).to(torch.bfloat16)
-                                           for a in (wl.q, wl.k, wl.v, wl.do))
-        self.bq, self.bk = (torch.from_numpy(a).to(dev) for a in (wl.lab_q, wl.lab_k))
+        if wl is not None:
+            dev = torch.device("cuda:0")
+            self.q, self.k, self.v, self.do = (torch.from_numpy(a).to(dev).to(torch.bfloat16)
+                                               for a in (wl.q, wl.k, wl.v, wl.do))
+            self.bq, self.bk = (torch.from_numpy(a).to(dev) for a in (wl.lab_q, wl.lab_k))
+            self.nb, self.tau = wl.nb, wl.tau
+        else:
+            self.q, self.k, self.v, self.do, self.bq, self.bk = tensors
+            self.nb, self.tau = nb, tau
         self.ctx = None
 
     def step(self):
-        o, lse, ctx = self.pipeline.hash_forward(self.q, self.k, self.v, self.bq, self.bk, self.wl.nb, self.wl.tau)
-        grads = self.pipeline.hash_backward(ctx, self.do)
+        if self.nb is None:
+            o, lse, ctx = self.pipeline.qkdrop_forward(self.q, self.k, self.v, self.bq, self.bk, self.tau)
+            grads = self.pipeline.qkdrop_backward(ctx, self.do)
+        else:
+            o, lse, ctx = self.pipeline.hash_forward(self.q, self.k, self.v, self.bq, self.bk, self.nb, self.tau)
+            grads = self.pipeline.hash_backward(ctx, self.do)
         self.ctx = ctx
         return o, lse, grads
 
@@ -137,6 +148,56 @@ def cpu_baseline(wl, n_seg):
             "fwd_s": t1 - t0, "bwd_s": t2 - t1}
 
 
+def sweep(kind, steps):
+    """Step time of the whole path against sparsity and sequence length, with the total number of
+    tokens held fixed, on random inputs drawn on the device (the form of the paper's runtime-in-a-
+    vacuum study, Sec. 4.2 / 4.3: buckets and drops given for free, uniformly random).  Speed-ups are
+    over the same code with one bucket / nothing dropped (dense causal) at the same T."""
+    import torch
+    from paper_2306_01160_amd import binding as sc
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device=dev); g.manual_seed(1234)
+    rows = []
+    if kind == "hash":
+        d, H, tokens = 64, 12, 24 * 16384
+        grid = [(T, nb) for T in (4096, 8192, 16384, 32768) for nb in (1, 2, 4, 8, 16, 32, 64)]
+    else:
+        d, H, tokens = 128, 16, 16 * 32768
+        grid = [(T, r) for T in (8192, 16384, 32768) for r in (1.0, 0.7, 0.5, 0.3, 0.1)]
+    tau = 1.0 / float(np.sqrt(d))
+    cache = {}
+    for T, par in grid:
+        B = tokens // (H * T)
+        if T not in cache:
+            cache.clear()
+            cache[T] = tuple((torch.randn((B, H, T, d), device=dev, generator=g) * 0.5).to(torch.bfloat16) for _ in range(4))
+        q, k, v, do = cache[T]
+        if kind == "hash":
+            lq = torch.randint(0, par, (B, H, T), device=dev, generator=g, dtype=torch.int32)
+            lk = torch.randint(0, par, (B, H, T), device=dev, generator=g, dtype=torch.int32)
+            job = HashJob(tensors=(q, k, v, do, lq, lk), nb=par, tau=tau)
+        else:
+            lq = (torch.rand((B, H, T), device=dev, generator=g) < par).to(torch.uint8)
+            lk = (torch.rand((B, H, T), device=dev, generator=g) < par).to(torch.uint8)
+            job = HashJob(tensors=(q, k, v, do, lq, lk), nb=None, tau=tau)
+        ms = job.timed(steps, 2)
+        kt = job.kernel_times(3)
+        attn = sum(kt[x]["ms_per_step"] for x in ("fwd", "bwd_dkdv", "bwd_dq"))
+        cnt = job.ctx.counters.cpu().numpy().sum(0)
+        fm, fn, bn, bm = sc.scfa_tile_config(d, sc.SCFA_BF16)
+        tile_flops = int(cnt[0]) * fm * fn * 6 * d + int(cnt[2]) * bm * bn * 8 * d
+        rows.append({"T": T, "B": B, "H": H, "d": d, ("nb" if kind == "hash" else "keep"): par, "ms_per_step": ms,
+                     "attn_kernels_ms": attn, "computed_tile_tflops_kernels": tile_flops / (attn * 1e-3) / 1e12})
+        log(f"[sweep] T={T} {par}: {ms:.3f} ms/step, attention kernels {attn:.3f} ms")
+        del job
+    dense = {r["T"]: r for r in rows if r.get("nb") == 1 or r.get("keep") == 1.0}
+    for r in rows:
+        r["speedup_end_to_end"] = dense[r["T"]]["ms_per_step"] / r["ms_per_step"]
+        r["speedup_kernels"] = dense[r["T"]]["attn_kernels_ms"] / r["attn_kernels_ms"]
+    print(json.dumps({"sweep": kind, "tokens_per_step": tokens, "dtype": "bf16", "data": "synthetic", "steps": steps,
+                      "rows": rows}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -146,9 +207,17 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-twin", action="store_true")
     ap.add_argument("--cpu-segments", type=int, default=6)
+    ap.add_argument("--sweep", default=None, choices=["hash", "qkdrop"])
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no sharding or collectives); use --gpus 1")
+    if args.sweep:
+        import torch
+        from paper_2306_01160_amd import binding as sc
+        if not torch.cuda.is_available():
+            sys.exit("bench.py: no GPU visible")
+        sc.lib()
+        return sweep(args.sweep, min(args.steps, 5))
 
     import torch
     from paper_2306_01160_amd import binding as sc
