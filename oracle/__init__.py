@@ -14,6 +14,10 @@ of kept tokens (paper Sec. 3.1, 3.2 and the pre-processing of App. B.2), the
 tile ranges of Alg. 1 and Alg. 2 taken in the paper's order, and brute-force
 tile occupancy.
 
+Bucketing (numpy, fp64): the cross-polytope LSH the paper adopts for its hash-sparse
+experiments (Sec. 4.2 "Hashing mechanism": the scheme of Andoni et al. with a chosen number
+of hash codes), in the form the benchmark definition states: argmax over [xR, -xR].
+
 Conventions: tensors are ``[S, T, d]`` float64 with ``S`` the flattened
 (batch, head) segments; labels are ``[S, T]`` int32 (bucket ids for the hash
 variant, 0/1 keep flags for QK-dropping).
@@ -315,3 +319,34 @@ def tile_occupancy(mask_perm, Bm, Bn):
 
 if __name__ == "__main__":
     print(build(force="--force" in sys.argv))
+
+
+# ---------------------------------------------------------------------------
+# LSH bucketing (the step in front of the hash-sparse path)
+# ---------------------------------------------------------------------------
+
+def lsh_projections(x, R, H):
+    """x [S,T,d], R [H,d,r] -> [S,T,2r] float64: for segment s = b*H + h the row x[s,t,:] times
+    R[h], followed by its negation (cross-polytope LSH: the 2r vertices +-e_c of the rotated
+    space, Sec. 4.2 "Hashing mechanism")."""
+    x = np.asarray(x, np.float64)
+    R = np.asarray(R, np.float64)
+    S, T, d = x.shape
+    assert R.shape[0] == H and R.shape[1] == d and S % H == 0
+    out = np.empty((S, T, 2 * R.shape[2]), np.float64)
+    for s in range(S):
+        p = x[s] @ R[s % H]
+        out[s, :, :R.shape[2]] = p
+        out[s, :, R.shape[2]:] = -p
+    return out
+
+
+def lsh_buckets(x, R, H):
+    """Bucket id = index of the largest entry of [xR, -xR]; the lowest index wins a tie.
+    Returns (bucket int32 [S,T], margin float64 [S,T]) with margin = largest minus second
+    largest entry (a caller comparing against lower-precision arithmetic uses it to set
+    aside rows whose decision is within rounding)."""
+    ext = lsh_projections(x, R, H)
+    b = np.argmax(ext, axis=-1).astype(np.int32)
+    part = np.partition(ext, -2, axis=-1)
+    return b, part[..., -1] - part[..., -2]

@@ -443,3 +443,59 @@ def test_paper_tile_ranges_cover_occupied_tiles():
         rg = oracle.paper_tile_ranges_qk(qv, kv, B, B)
         for i, (a, e) in enumerate(rg):
             assert all(a <= c < e for c in np.flatnonzero(occ[i]))
+
+
+# ---------------------------------------------------------------- LSH bucketing pins
+
+def test_lsh_axis_aligned_projection_is_signed_argmax_abs():
+    """With R = the first r columns of the identity, [xR, -xR] = [x_0..x_{r-1}, -x_0..-x_{r-1}]:
+    the bucket is the coordinate of largest magnitude, offset by r when it is negative
+    (catches a transposed R, a missing negated half, a wrong concatenation order)."""
+    d, r, T = 8, 4, 200
+    x = rnd(21, 2, T, d)
+    R = np.zeros((1, d, r)); R[0, :r, :r] = np.eye(r)
+    b, margin = oracle.lsh_buckets(x, R, 1)
+    c = np.argmax(np.abs(x[..., :r]), axis=-1)
+    expect = np.where(np.take_along_axis(x[..., :r], c[..., None], -1)[..., 0] >= 0, c, c + r)
+    assert np.array_equal(b, expect) and (margin >= 0).all()
+
+
+def test_lsh_hand_example_and_tie_rule():
+    """x = (1, 2), R = [[1, 0], [0, 1]]: [1, 2, -1, -2] -> bucket 1; x = (-3, 1): [-3, 1, 3, -1] -> 2;
+    x = (1, 1): a tie between entries 0 and 1 -> the lowest index; x = 0: every entry ties -> 0."""
+    R = np.eye(2)[None]
+    x = np.array([[[1.0, 2.0], [-3.0, 1.0], [1.0, 1.0], [0.0, 0.0]]])
+    b, margin = oracle.lsh_buckets(x, R, 1)
+    assert b[0].tolist() == [1, 2, 0, 0]
+    assert margin[0].tolist() == [1.0, 2.0, 0.0, 0.0]
+
+
+def test_lsh_invariances_and_per_head_projection():
+    """Positive scaling leaves the bucket, negation moves it to the antipodal vertex (c <-> c + r);
+    segment s uses the projection of head s % H (catches indexing R by batch instead of head)."""
+    H, d, r, T = 3, 16, 4, 300
+    x = rnd(22, 2 * H, T, d)
+    R = rnd(23, H, d, r)
+    b, _ = oracle.lsh_buckets(x, R, H)
+    assert np.array_equal(oracle.lsh_buckets(3.7 * x, R, H)[0], b)
+    assert np.array_equal(oracle.lsh_buckets(-x, R, H)[0], (b + r) % (2 * r))
+    for s in range(2 * H):
+        assert np.array_equal(oracle.lsh_buckets(x[s:s + 1], R[s % H:s % H + 1], 1)[0][0], b[s])
+    # with orthonormal columns the projections of Gaussian rows are i.i.d. N(0,1): all 2r vertices
+    # are equally likely (12000 rows: three standard deviations of a frequency are below 0.01)
+    Q = np.linalg.qr(rnd(24, d, d))[0][None, :, :r]
+    bu, _ = oracle.lsh_buckets(rnd(25, 1, 12000, d), Q, 1)
+    counts = np.bincount(bu.ravel(), minlength=2 * r) / bu.size
+    assert np.abs(counts - 1.0 / (2 * r)).max() < 0.012
+
+
+def test_lsh_matches_generator_of_the_benchmark_inputs():
+    """The workload generator draws its bucket ids with its own implementation of the same rule;
+    the two agree wherever the decision is not within rounding."""
+    from paper_2306_01160_amd import workloads as W
+    wl = W.hash_lsh(9, 2, 3, 256, 64, 8)
+    Rm = np.random.default_rng(5).standard_normal((3, 64, 4)).astype(np.float32)
+    got = W.lsh_buckets(wl.q, Rm).reshape(6, 256)
+    ref, margin = oracle.lsh_buckets(wl.q.reshape(6, 256, 64), Rm, 3)
+    clear = margin > 1e-9
+    assert clear.mean() > 0.99 and np.array_equal(got[clear], ref[clear])
