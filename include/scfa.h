@@ -99,6 +99,24 @@ int scfa_sort_by_bucket_pair(const int32_t *bucket_q, const int32_t *bucket_k,
                              void *stream);
 
 /* ------------------------------------------------------------------------
+ * a0. LSH bucketing, the step in front of the hash-sparse path (Sec. 4.2 "Hashing
+ * mechanism": the cross-polytope scheme of Andoni et al. with a chosen number of hash
+ * codes).  For every row x[s,t,:] and the projection R[h] of its head h = s % H:
+ *     bucket[s,t] = argmax over the 2r values [x R[h], -x R[h]],  r = nb / 2,
+ * the lowest index winning a tie, i.e. a value in [0, nb).
+ *
+ *   x_q, x_k    [S,T,d] SCFA_BF16 or SCFA_F32; x_k (and bucket_k_out) may be NULL: one tensor
+ *   R           [H,d,r] float32, row-major (d rows of r columns per head)
+ *   bucket_*_out [S,T] int32
+ * The projections are formed in fp32; a row whose two largest candidates differ by less
+ * than fp32 rounding of the dot products may land on either of them.
+ * Limits: nb even, 2 <= nb <= SCFA_MAX_BUCKETS, d in {64, 128}, S % H == 0, d * r * 4 <= 64 KiB.
+ */
+int scfa_lsh_buckets(const void *x_q, const void *x_k, const float *R,
+                     int S, int H, int T, int d, int nb, int dtype,
+                     int32_t *bucket_q_out, int32_t *bucket_k_out, void *stream);
+
+/* ------------------------------------------------------------------------
  * a2. Compaction for QK-dropping (Sec. 3.1, "Shrinking the attention matrix").
  *
  *   keep       [S,T] uint8, non-zero = kept
@@ -298,7 +316,8 @@ int scfa_qkdrop_attn_bwd(const void *q_c, const void *k_c, const void *v_c,
 #define SCFA_K_BWD_DKDV    6
 #define SCFA_K_BWD_DQ      7
 #define SCFA_K_FILL        8
-#define SCFA_K_COUNT       9
+#define SCFA_K_LSH         9
+#define SCFA_K_COUNT       10
 
 int scfa_prof_enable(int on);      /* returns the previous state */
 int scfa_prof_reset(void);

@@ -23,11 +23,11 @@ SCFA_HASH, SCFA_QKDROP = 0, 1
 SCFA_FLAG_STRICT_CAUSAL = 1
 SCFA_WORK_STRIDE = 8
 KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_prep": 5,
-              "bwd_dkdv": 6, "bwd_dq": 7, "fill": 8}
+              "bwd_dkdv": 6, "bwd_dq": 7, "fill": 8, "lsh": 9}
 
 EXPORTS = [
     "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket",
-    "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv",
+    "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv", "scfa_lsh_buckets",
     "scfa_compact_keep", "scfa_q_scale", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
     "scfa_attn_bwd_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
@@ -55,6 +55,7 @@ def lib():
         L.scfa_error_string.argtypes = [ci]
         L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp]
+        L.scfa_lsh_buckets.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
         L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
         L.scfa_compact_keep_pair.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
         L.scfa_gather_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
@@ -130,6 +131,16 @@ def scfa_tile_config(d: int, dtype: int):
     _check(lib().scfa_tile_config(d, dtype, ctypes.byref(a), ctypes.byref(b), ctypes.byref(c), ctypes.byref(e)),
            "scfa_tile_config")
     return a.value, b.value, c.value, e.value
+
+
+def scfa_lsh_buckets(x_q: torch.Tensor, x_k, R: torch.Tensor, H: int, nb: int):
+    """x_q, x_k [S,T,d] (x_k may be None), R [H,d,nb/2] float32 -> bucket ids int32 [S,T] (one or two)."""
+    S, T, d = x_q.shape
+    assert R.dtype == torch.float32 and tuple(R.shape) == (H, d, nb // 2)
+    out = torch.empty((2 if x_k is not None else 1, S, T), dtype=torch.int32, device=x_q.device)
+    _check(lib().scfa_lsh_buckets(_ptr(x_q), _ptr(x_k), _ptr(R), S, H, T, d, nb, dtype_code(x_q), _ptr(out[0]),
+                                  _ptr(out[1]) if x_k is not None else None, _stream()), "scfa_lsh_buckets")
+    return (out[0], out[1]) if x_k is not None else out[0]
 
 
 def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int):

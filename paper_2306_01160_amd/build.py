@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ_DIR = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libscfa.so")
 
-SOURCES = ["scfa_api.hip", "scfa_index.hip", "scfa_ranges.hip", "scfa_attn_f32.hip", "scfa_attn_fwd.hip",
+SOURCES = ["scfa_api.hip", "scfa_index.hip", "scfa_lsh.hip", "scfa_ranges.hip", "scfa_attn_f32.hip", "scfa_attn_fwd.hip",
            "scfa_attn_bwd.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

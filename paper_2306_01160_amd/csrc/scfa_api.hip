@@ -196,6 +196,20 @@ int scfa_compact_keep_pair(const uint8_t* keep_q, const uint8_t* keep_k, int S, 
     return launch_compact_keep(2, keep_q, keep_k, S, T, q_idx_out, n_q_out, k_idx_out, n_k_out, (hipStream_t)stream);
 }
 
+int scfa_lsh_buckets(const void* x_q, const void* x_k, const float* R, int S, int H, int T, int d, int nb, int dtype,
+                     int32_t* bucket_q_out, int32_t* bucket_k_out, void* stream)
+{
+    if (!x_q || !R || !bucket_q_out || S <= 0 || H <= 0 || T <= 0 || nb <= 0) return SCFA_EINVAL;
+    if ((x_k == nullptr) != (bucket_k_out == nullptr)) return SCFA_EINVAL;
+    if (S % H != 0 || (nb & 1) != 0) return SCFA_EINVAL;
+    if (!aligned16(x_q) || !aligned16(x_k)) return SCFA_EINVAL;
+    if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
+    if (d != 64 && d != 128) return SCFA_EUNSUPPORTED;
+    if (nb > SCFA_MAX_BUCKETS || (size_t)d * (nb / 2) * 4 > 64 * 1024 || S > 65535) return SCFA_EUNSUPPORTED;
+    return launch_lsh_buckets(x_k ? 2 : 1, x_q, x_k, R, S, H, T, d, nb, dtype == SCFA_BF16, bucket_q_out,
+                              bucket_k_out, (hipStream_t)stream);
+}
+
 float scfa_q_scale(float tau) { return tau * 1.4426950408889634f; }
 
 int scfa_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T, int d, int dtype,

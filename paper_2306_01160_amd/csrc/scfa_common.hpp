@@ -54,6 +54,8 @@ int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t*
                           int32_t* off1, hipStream_t st);
 int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
                         int32_t* count0, int32_t* idx1, int32_t* count1, hipStream_t st);
+int launch_lsh_buckets(int n_problems, const void* x0, const void* x1, const float* R, int S, int H, int T, int d,
+                       int nb, bool bf16, int32_t* out0, int32_t* out1, hipStream_t st);
 int launch_gather_rows(int n_tensors, const void* const* x, const int32_t* const* idx, const int32_t* const* count,
                        const float* scale, void* const* out, int S, int T, int row_bytes, int mode, hipStream_t st);
 int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,

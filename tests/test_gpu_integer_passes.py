@@ -159,6 +159,51 @@ def test_pair_entry_points_match_single_calls(S, T, nb):
             assert torch.equal(g_k[s_, :b], r_k[s_, :b]) and torch.equal(g_v[s_, :b], r_v[s_, :b])
 
 
+# ------------------------------------------------------------------ LSH bucketing
+
+@pytest.mark.parametrize("S,H,T,d,nb,dtype", [(4, 2, 1000, 64, 8, torch.bfloat16), (3, 3, 777, 128, 16, torch.bfloat16),
+                                               (2, 1, 4096, 64, 2, torch.bfloat16), (2, 2, 513, 64, 64, torch.float32),
+                                               (1, 1, 1, 64, 4, torch.bfloat16), (2, 2, 300, 128, 256, torch.float32)])
+def test_lsh_buckets_against_oracle(S, H, T, d, nb, dtype):
+    """argmax over [xR, -xR]: an integer decided by floating point.  The kernel decides in fp32, the
+    oracle in fp64, so: wherever the oracle's two largest candidates are further apart than fp32
+    rounding of a d-term dot product can move them, the ids are equal; everywhere, the id the
+    kernel picked is a candidate within that rounding of the oracle's maximum."""
+    rng = np.random.default_rng(S * 100 + T + nb)
+    x = torch.from_numpy(rng.standard_normal((S, T, d)).astype(np.float32)).to(DEV).to(dtype)
+    y = torch.from_numpy(rng.standard_normal((S, T, d)).astype(np.float32)).to(DEV).to(dtype)
+    R = rng.standard_normal((H, d, nb // 2)).astype(np.float32)
+    bx, by = sc.scfa_lsh_buckets(x, y, _t(R), H, nb)
+    bx1 = sc.scfa_lsh_buckets(x, None, _t(R), H, nb)
+    assert torch.equal(bx, bx1)
+    for t, got in ((x, bx), (y, by)):
+        x64 = t.float().cpu().numpy().astype(np.float64)
+        ref, margin = oracle.lsh_buckets(x64, R, H)
+        ext = oracle.lsh_projections(x64, R, H)
+        got = got.cpu().numpy()
+        assert got.min() >= 0 and got.max() < nb
+        eps = 64 * np.finfo(np.float32).eps * np.abs(x64).sum(-1) * np.abs(R).max()     # generous fp32 bound
+        clear = margin > eps
+        assert clear.mean() > 0.95
+        assert np.array_equal(got[clear], ref[clear])
+        picked = np.take_along_axis(ext, got[..., None].astype(np.int64), -1)[..., 0]
+        assert (picked >= ext.max(-1) - eps).all()
+
+
+def test_lsh_buckets_exact_ties_take_the_lowest_index():
+    """Rows and projections of small integers: every product and sum is exact in fp32, so ties are
+    real ties and the ids must equal the oracle's bit for bit."""
+    rng = np.random.default_rng(3)
+    S, H, T, d, nb = 2, 2, 640, 64, 8
+    x = torch.from_numpy(rng.integers(-2, 3, (S, T, d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
+    x[0, :4] = 0                                     # all candidates tie at zero -> bucket 0
+    R = rng.integers(-1, 2, (H, d, nb // 2)).astype(np.float32)
+    got = sc.scfa_lsh_buckets(x, None, _t(R), H, nb).cpu().numpy()
+    ref, margin = oracle.lsh_buckets(x.float().cpu().numpy(), R, H)
+    assert (margin == 0).sum() > 10                  # the case does contain ties
+    assert np.array_equal(got, ref)
+
+
 # ------------------------------------------------------------------ schedule
 
 def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
