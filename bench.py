@@ -206,7 +206,7 @@ def main():
     ap.add_argument("--workload", default="c4", choices=["c4", "c3"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-twin", action="store_true")
-    ap.add_argument("--cpu-segments", type=int, default=6)
+    ap.add_argument("--cpu-segments", type=int, default=24)
     ap.add_argument("--sweep", default=None, choices=["hash", "qkdrop"])
     args = ap.parse_args()
     if args.gpus != 1:
