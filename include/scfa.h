@@ -189,15 +189,15 @@ int scfa_gather_qkv(const void *q, const void *k, const void *v,
  *     [k_begin, k_begin+k_count): the keys of the same bucket whose position is
  *     <= the LARGEST query position of the item.  The first k_nomask of these
  *     keys have a position <= the SMALLEST query position: no mask needed.
- *     Items of a segment are ordered by decreasing k_count; unused trailing
- *     items have q_count == 0.
+ *     Items of a segment are ordered by bucket pair (bucket / 2) and, inside a pair,
+ *     by decreasing k_count; unused trailing items have q_count == 0.
  *   bwd_work_out [S, n_bwd, 8] int32 (nullable), n_bwd = scfa_num_work_items(T, nb, bwd_tile_n).
  *     Item = { k_begin, k_count, q_begin, q_count, q_masked, bucket, 0, 0 }:
  *     permuted key rows [k_begin, k_begin+k_count) are attended by permuted
  *     query rows [q_begin, q_begin+q_count): the queries of the same bucket
  *     whose position is >= the SMALLEST key position of the item.  Only the
  *     first q_masked of them (position < the LARGEST key position) need a mask.
- *     Ordered by decreasing q_count.
+ *     Ordered by bucket pair and, inside a pair, by decreasing q_count.
  *   counters_out [S,4] int64 (nullable): { forward tiles of fwd_tile_m x fwd_tile_n,
  *     sum of q_count*k_count, backward tiles of bwd_tile_m x bwd_tile_n, sum of
  *     k_count*q_count } -- the "computed tile" counts throughput is quoted on.

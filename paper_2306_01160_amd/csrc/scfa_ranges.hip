@@ -11,8 +11,12 @@
 //                  (and the prefix with position <= smallest query position needs no mask)
 //   backward item: queries with position >= smallest key position of the tile
 //                  (only those with position < largest key position need a mask)
-// Items of a segment are emitted in order of decreasing work so that the long
-// ones are dispatched first.
+// Items of a segment are emitted bucket pair by bucket pair, and inside a pair in order of
+// decreasing work.  Workgroups that run at the same time then share the keys / values
+// (forward) or queries / dO rows (backward) of one or two buckets, which stay in the L2 of
+// their XCD (measured at 8 buckets of 2048: 0.15-0.2 GB fetched from memory per attention
+// kernel instead of 0.6 GB with a purely work-ordered list), while the last workgroups of a
+// launch are still the short items.
 //
 // One workgroup builds one list of one segment (the forward and the backward list are
 // independent).  The index vector that is searched is first copied into LDS when it fits,
@@ -45,7 +49,15 @@ __device__ __forceinline__ int count_lt(const int32_t* __restrict__ a, int n, in
     return lo;
 }
 
+constexpr int ORDER_GROUP = 2;   // buckets whose items are dispatched together
+
 struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket; };
+
+// ascending sort key: bucket pair first, then decreasing length of the ranged side (< 2^24)
+__device__ __forceinline__ int order_key(int bucket, int b_count)
+{
+    return ((bucket / ORDER_GROUP) << 24) | (0xffffff - min(b_count, 0xffffff));
+}
 
 // Builds one work list.  "a" is the tiled side (queries forward, keys backward),
 // "b" the ranged side.
@@ -100,18 +112,21 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_i
         return it;
     };
 
-    for (int w = threadIdx.x; w < n_items; w += RANGES_THREADS) s_cost[w] = make_item(w).b_count;
+    for (int w = threadIdx.x; w < n_items; w += RANGES_THREADS) {
+        const Item it = make_item(w);
+        s_cost[w] = order_key(it.bucket, it.b_count);
+    }
     __syncthreads();
 
     long long tiles = 0, rect = 0;
     for (int w = threadIdx.x; w < n_items_max; w += RANGES_THREADS) {
         if (w < n_items) {
             const Item it = make_item(w);
-            const int c = it.b_count;
+            const int c = order_key(it.bucket, it.b_count);
             int rank = 0;
             for (int u = 0; u < n_items; ++u) {
                 const int cu = s_cost[u];
-                rank += (cu > c) || (cu == c && u < w);
+                rank += (cu < c) || (cu == c && u < w);
             }
             int32_t* o = work_out + (size_t)rank * WORK_STRIDE;
             o[0] = it.a_begin; o[1] = it.a_count; o[2] = it.b_begin; o[3] = it.b_count;
@@ -150,8 +165,9 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int32_t* s_qoff = smem;                   // [nb+1]
     int32_t* s_koff = s_qoff + nb + 1;        // [nb+1]
     int32_t* s_tile_base = s_koff + nb + 1;   // [nb+1]
+    const int n_max_items = n_fwd > n_bwd ? n_fwd : n_bwd;
     int32_t* s_cost = s_tile_base + nb + 1;   // [max(n_fwd, n_bwd)]
-    int32_t* s_idx = smem + ((3 * (nb + 1) + (n_fwd > n_bwd ? n_fwd : n_bwd) + 3) & ~3);   // [T] when staged, 16-byte aligned
+    int32_t* s_idx = smem + ((3 * (nb + 1) + n_max_items + 3) & ~3);   // [T] when staged, 16-byte aligned
     const int s = blockIdx.x;
     const bool backward = blockIdx.y == 1;
     if (variant == SCFA_QKDROP) {

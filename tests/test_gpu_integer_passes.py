@@ -206,10 +206,18 @@ def test_lsh_buckets_exact_ties_take_the_lowest_index():
 
 # ------------------------------------------------------------------ schedule
 
+def _check_order(live):
+    """items come bucket pair by bucket pair; inside a pair the ranged side's count never grows"""
+    group = live[:, 5] // 2
+    assert np.all(np.diff(group) >= 0), "items must be grouped by bucket pair"
+    same = np.diff(group) == 0
+    assert np.all(np.diff(live[:, 3])[same] <= 0), "inside a bucket pair items must be ordered by decreasing work"
+
+
 def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
     """Several schedules are correct; check what must hold: every allowed pair is covered
     exactly once, claimed mask-free regions are mask-free, ranges are tight, items are
-    ordered by decreasing work, counters match the emitted items."""
+    ordered by bucket pair and by decreasing work inside a pair, counters match the emitted items."""
     fm, fn, bn, bm = tiles
     S, T = lab_q.shape
     if variant == sc.SCFA_HASH:
@@ -236,7 +244,7 @@ def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
         items = fwd[s]
         live = items[items[:, 1] > 0]
         assert np.all(items[len(live):] == 0), "unused items must trail and be zero"
-        assert np.all(np.diff(live[:, 3]) <= 0), "forward items must be ordered by decreasing k_count"
+        _check_order(live)
         tiles_f = 0; rect_f = 0
         for qb, qc, kb, kc, kn, bucket, _, _ in live:
             assert 0 < qc <= fm and 0 <= kn <= kc
@@ -255,7 +263,7 @@ def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
         items = bwd[s]
         live = items[items[:, 1] > 0]
         assert np.all(items[len(live):] == 0)
-        assert np.all(np.diff(live[:, 3]) <= 0)
+        _check_order(live)
         tiles_b = 0; rect_b = 0
         for kb, kc, qb, qc, qm, bucket, _, _ in live:
             assert 0 < kc <= bn and 0 <= qm <= qc
