@@ -238,9 +238,10 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  *   o_out                 [B,H,T,d] in ORIGINAL order, dtype of the inputs
  *   lse_out               [B,H,T] float, ORIGINAL order: natural-log logsumexp of the
  *                         scaled scores over allowed keys; -inf for a row with none
- *   o_f32_out             [B,H,T,d] float (nullable, SCFA_BF16 only): the same O before its
- *                         rounding to bf16, for the backward's D = <dO, O>; pass it to the
- *                         backward as o_f32.  Rows of dropped queries are not written.
+ *   o_f16_out             [B,H,T,d] fp16 (nullable, SCFA_BF16 only): the same O rounded to fp16
+ *                         (11 significant bits instead of bf16's 8), for the backward's
+ *                         D = <dO, O>; pass it to the backward as o_f16.  Rows of dropped
+ *                         queries are not written.
  * d: 64 or 128.  SCFA_BF16: scores are bf16 x bf16 products accumulated in fp32; P is
  * rounded to fp16 and V converted to fp16 (exact for |v| in [2^-14, 65504]) for P.V.
  *
@@ -251,13 +252,13 @@ int scfa_hash_attn_fwd(const void *q_perm, const void *k_perm, const void *v_per
                        const int32_t *q_idx, const int32_t *k_idx,
                        const int32_t *fwd_work, int n_fwd,
                        int B, int H, int T, int d, int dtype, float sm_scale, int flags,
-                       void *o_out, float *lse_out, float *o_f32_out, void *stream);
+                       void *o_out, float *lse_out, void *o_f16_out, void *stream);
 
 int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
                          const int32_t *q_idx, const int32_t *k_idx, const int32_t *n_q,
                          const int32_t *fwd_work, int n_fwd,
                          int B, int H, int T, int d, int dtype, float sm_scale, int flags,
-                         void *o_out, float *lse_out, float *o_f32_out, void *stream);
+                         void *o_out, float *lse_out, void *o_f16_out, void *stream);
 
 /* ------------------------------------------------------------------------
  * a6 + a7 (+a8). Backward.  The paper states the backward is adapted like the
@@ -267,7 +268,7 @@ int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
  *   dQ_i = tau sum_j dS_ij K_j,  dK_j = tau sum_i dS_ij Q_i,  dV_j = sum_i P_ij dO_i.
  *
  *   o, lse        outputs of the forward (ORIGINAL order)
- *   o_f32         (nullable) the forward's o_f32_out; when given, D is computed from it
+ *   o_f16         (nullable) the forward's o_f16_out; when given, D is computed from it
  *                 instead of the bf16-rounded o (tighter gradients), and o may be NULL
  *   d_o           [B,H,T,d] upstream gradient, ORIGINAL order, dtype of the inputs
  *   dq_out, dk_out, dv_out   [B,H,T,d] FLOAT32, ORIGINAL order; rows of dropped or
@@ -288,7 +289,7 @@ int scfa_hash_attn_bwd(const void *q_perm, const void *k_perm, const void *v_per
                        const int32_t *q_idx, const int32_t *k_idx,
                        const int32_t *fwd_work, int n_fwd,
                        const int32_t *bwd_work, int n_bwd,
-                       const void *o, const float *o_f32, const float *lse, const void *d_o,
+                       const void *o, const void *o_f16, const float *lse, const void *d_o,
                        int B, int H, int T, int d, int dtype, float sm_scale, int flags,
                        float *dq_out, float *dk_out, float *dv_out,
                        void *ws, size_t ws_bytes, void *stream);
@@ -298,7 +299,7 @@ int scfa_qkdrop_attn_bwd(const void *q_c, const void *k_c, const void *v_c,
                          const int32_t *n_q, const int32_t *n_k,
                          const int32_t *fwd_work, int n_fwd,
                          const int32_t *bwd_work, int n_bwd,
-                         const void *o, const float *o_f32, const float *lse, const void *d_o,
+                         const void *o, const void *o_f16, const float *lse, const void *d_o,
                          int B, int H, int T, int d, int dtype, float sm_scale, int flags,
                          float *dq_out, float *dk_out, float *dv_out,
                          void *ws, size_t ws_bytes, void *stream);

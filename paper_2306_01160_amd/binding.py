@@ -234,27 +234,27 @@ def scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles, want_bwd=T
 
 
 def scfa_hash_attn_fwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, B, H, sm_scale, o_out=None, lse_out=None,
-                       o_f32_out=None, flags=0):
+                       o_f16_out=None, flags=0):
     S, T, d = q_perm.shape
     assert S == B * H
     o = torch.empty((B, H, T, d), dtype=_out_dtype(q_perm), device=q_perm.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_perm.device) if lse_out is None else lse_out
     _check(lib().scfa_hash_attn_fwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
                                     _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_perm),
-                                    float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f32_out), _stream()),
+                                    float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f16_out), _stream()),
            "scfa_hash_attn_fwd")
     return o, lse
 
 
 def scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_out=None, lse_out=None,
-                         o_f32_out=None, flags=0):
+                         o_f16_out=None, flags=0):
     S, T, d = q_c.shape
     assert S == B * H
     o = torch.empty((B, H, T, d), dtype=_out_dtype(q_c), device=q_c.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_c.device) if lse_out is None else lse_out
     _check(lib().scfa_qkdrop_attn_fwd(_ptr(q_c), _ptr(k_c), _ptr(v_c), _ptr(q_idx), _ptr(k_idx), _ptr(n_q),
                                       _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_c),
-                                      float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f32_out), _stream()),
+                                      float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f16_out), _stream()),
            "scfa_qkdrop_attn_fwd")
     return o, lse
 
@@ -270,7 +270,7 @@ def _bwd_outputs(B, H, T, d, dev, outs):
 
 
 def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, bwd_work, o, lse, d_o, B, H, sm_scale,
-                       ws=None, outs=None, o_f32=None, flags=0):
+                       ws=None, outs=None, o_f16=None, flags=0):
     S, T, d = q_perm.shape
     dt = dtype_code(q_perm)
     need = scfa_attn_bwd_workspace_bytes(S, T, d, dt)
@@ -279,14 +279,14 @@ def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, bwd_work,
     dq, dk, dv = _bwd_outputs(B, H, T, d, q_perm.device, outs)
     _check(lib().scfa_hash_attn_bwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
                                     _ptr(fwd_work), fwd_work.shape[1], _ptr(bwd_work), bwd_work.shape[1],
-                                    _ptr(o), _ptr(o_f32), _ptr(lse), _ptr(d_o), B, H, T, d, dt, float(sm_scale),
+                                    _ptr(o), _ptr(o_f16), _ptr(lse), _ptr(d_o), B, H, T, d, dt, float(sm_scale),
                                     int(flags), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()),
            "scfa_hash_attn_bwd")
     return dq, dk, dv
 
 
 def scfa_qkdrop_attn_bwd(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work, o, lse, d_o, B, H, sm_scale,
-                         ws=None, outs=None, o_f32=None, flags=0):
+                         ws=None, outs=None, o_f16=None, flags=0):
     S, T, d = q_c.shape
     dt = dtype_code(q_c)
     need = scfa_attn_bwd_workspace_bytes(S, T, d, dt)
@@ -295,7 +295,7 @@ def scfa_qkdrop_attn_bwd(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_wo
     dq, dk, dv = _bwd_outputs(B, H, T, d, q_c.device, outs)
     _check(lib().scfa_qkdrop_attn_bwd(_ptr(q_c), _ptr(k_c), _ptr(v_c), _ptr(q_idx), _ptr(k_idx), _ptr(n_q),
                                       _ptr(n_k), _ptr(fwd_work), fwd_work.shape[1], _ptr(bwd_work),
-                                      bwd_work.shape[1], _ptr(o), _ptr(o_f32), _ptr(lse), _ptr(d_o), B, H, T, d, dt,
+                                      bwd_work.shape[1], _ptr(o), _ptr(o_f16), _ptr(lse), _ptr(d_o), B, H, T, d, dt,
                                       float(sm_scale), int(flags), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(),
                                       _stream()), "scfa_qkdrop_attn_bwd")
     return dq, dk, dv

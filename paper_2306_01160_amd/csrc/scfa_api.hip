@@ -74,13 +74,13 @@ static int check_attn_common(const void* q, const void* k, const void* v, const 
 static int attn_fwd_impl(const void* q, const void* k, const void* v, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* n_q, bool qkdrop, const int32_t* work,
                          int n_work, int B, int H, int T, int d, int dtype, float sm_scale, int flags,
-                         void* o, float* lse, float* o_f32, hipStream_t st)
+                         void* o, float* lse, void* o_f16, hipStream_t st)
 {
     int rc = check_attn_common(q, k, v, q_idx, k_idx, work, n_work, B, H, T, d, dtype, sm_scale, flags);
     if (rc != SCFA_OK) return rc;
     if (!o || !lse || !aligned16(o)) return SCFA_EINVAL;
     if (qkdrop && !n_q) return SCFA_EINVAL;
-    if (o_f32 && (dtype != SCFA_BF16 || !aligned16(o_f32))) return SCFA_EINVAL;
+    if (o_f16 && (dtype != SCFA_BF16 || !aligned16(o_f16))) return SCFA_EINVAL;
     const int S = B * H;
     const int esize = dtype == SCFA_BF16 ? 2 : 4;
     if (qkdrop) {
@@ -91,20 +91,20 @@ static int attn_fwd_impl(const void* q, const void* k, const void* v, const int3
         return launch_attn_fwd_f32((const float*)q, (const float*)k, (const float*)v, q_idx, k_idx, work,
                                    n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, (float*)o, lse, st);
     return launch_attn_fwd_bf16(q, k, v, q_idx, k_idx, work, n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, o,
-                                lse, o_f32, st);
+                                lse, o_f16, st);
 }
 
 static int attn_bwd_impl(const void* q, const void* k, const void* v, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* n_q, const int32_t* n_k, bool qkdrop,
                          const int32_t* fwd_work, int n_fwd, const int32_t* bwd_work, int n_bwd,
-                         const void* o, const float* o_f32, const float* lse, const void* d_o, int B, int H,
+                         const void* o, const void* o_f16, const float* lse, const void* d_o, int B, int H,
                          int T, int d, int dtype, float sm_scale, int flags, float* dq, float* dk, float* dv,
                          void* ws, size_t ws_bytes, hipStream_t st)
 {
     int rc = check_attn_common(q, k, v, q_idx, k_idx, fwd_work, n_fwd, B, H, T, d, dtype, sm_scale, flags);
     if (rc != SCFA_OK) return rc;
-    if (!bwd_work || n_bwd <= 0 || (!o && !o_f32) || !lse || !d_o || !dq || !dk || !dv || !ws) return SCFA_EINVAL;
-    if (!aligned16(o) || !aligned16(o_f32) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv)) return SCFA_EINVAL;
+    if (!bwd_work || n_bwd <= 0 || (!o && !o_f16) || !lse || !d_o || !dq || !dk || !dv || !ws) return SCFA_EINVAL;
+    if (!aligned16(o) || !aligned16(o_f16) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv)) return SCFA_EINVAL;
     if ((reinterpret_cast<uintptr_t>(ws) & 255u) != 0) return SCFA_EINVAL;
     if (qkdrop && (!n_q || !n_k)) return SCFA_EINVAL;
     if (dtype != SCFA_BF16) return SCFA_EUNSUPPORTED;
@@ -131,7 +131,7 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
         rc = launch_zero_rows(k_idx, n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
     }
-    rc = launch_bwd_prep_bf16(o, o_f32, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
+    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
     rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, d,
                                    flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
@@ -298,20 +298,20 @@ int scfa_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx, c
 
 int scfa_hash_attn_fwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,
                        const int32_t* k_idx, const int32_t* fwd_work, int n_fwd, int B, int H, int T, int d,
-                       int dtype, float sm_scale, int flags, void* o_out, float* lse_out, float* o_f32_out,
+                       int dtype, float sm_scale, int flags, void* o_out, float* lse_out, void* o_f16_out,
                        void* stream)
 {
     return attn_fwd_impl(q_perm, k_perm, v_perm, q_idx, k_idx, nullptr, false, fwd_work, n_fwd, B, H, T, d, dtype,
-                         sm_scale, flags, o_out, lse_out, o_f32_out, (hipStream_t)stream);
+                         sm_scale, flags, o_out, lse_out, o_f16_out, (hipStream_t)stream);
 }
 
 int scfa_qkdrop_attn_fwd(const void* q_c, const void* k_c, const void* v_c, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* n_q, const int32_t* fwd_work, int n_fwd, int B,
                          int H, int T, int d, int dtype, float sm_scale, int flags, void* o_out, float* lse_out,
-                         float* o_f32_out, void* stream)
+                         void* o_f16_out, void* stream)
 {
     return attn_fwd_impl(q_c, k_c, v_c, q_idx, k_idx, n_q, true, fwd_work, n_fwd, B, H, T, d, dtype, sm_scale,
-                         flags, o_out, lse_out, o_f32_out, (hipStream_t)stream);
+                         flags, o_out, lse_out, o_f16_out, (hipStream_t)stream);
 }
 
 size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype)
@@ -323,22 +323,22 @@ size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype)
 
 int scfa_hash_attn_bwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,
                        const int32_t* k_idx, const int32_t* fwd_work, int n_fwd, const int32_t* bwd_work,
-                       int n_bwd, const void* o, const float* o_f32, const float* lse, const void* d_o, int B,
+                       int n_bwd, const void* o, const void* o_f16, const float* lse, const void* d_o, int B,
                        int H, int T, int d, int dtype, float sm_scale, int flags, float* dq_out, float* dk_out,
                        float* dv_out, void* ws, size_t ws_bytes, void* stream)
 {
     return attn_bwd_impl(q_perm, k_perm, v_perm, q_idx, k_idx, nullptr, nullptr, false, fwd_work, n_fwd, bwd_work,
-                         n_bwd, o, o_f32, lse, d_o, B, H, T, d, dtype, sm_scale, flags, dq_out, dk_out, dv_out, ws,
+                         n_bwd, o, o_f16, lse, d_o, B, H, T, d, dtype, sm_scale, flags, dq_out, dk_out, dv_out, ws,
                          ws_bytes, (hipStream_t)stream);
 }
 
 int scfa_qkdrop_attn_bwd(const void* q_c, const void* k_c, const void* v_c, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* n_q, const int32_t* n_k, const int32_t* fwd_work,
-                         int n_fwd, const int32_t* bwd_work, int n_bwd, const void* o, const float* o_f32,
+                         int n_fwd, const int32_t* bwd_work, int n_bwd, const void* o, const void* o_f16,
                          const float* lse, const void* d_o, int B, int H, int T, int d, int dtype, float sm_scale, int flags,
                          float* dq_out, float* dk_out, float* dv_out, void* ws, size_t ws_bytes, void* stream)
 {
-    return attn_bwd_impl(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, true, fwd_work, n_fwd, bwd_work, n_bwd, o, o_f32, lse, d_o,
+    return attn_bwd_impl(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, true, fwd_work, n_fwd, bwd_work, n_bwd, o, o_f16, lse, d_o,
                          B, H, T, d, dtype, sm_scale, flags, dq_out, dk_out, dv_out, ws, ws_bytes,
                          (hipStream_t)stream);
 }

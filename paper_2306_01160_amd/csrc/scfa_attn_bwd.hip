@@ -37,6 +37,7 @@ namespace scfa {
 // ===========================================================================
 // Pre-pass
 // ===========================================================================
+using f16x8h = _Float16 __attribute__((ext_vector_type(8)));
 constexpr int AMAX_BLOCKS = 64;   // partial maxima per segment
 
 // partial[s][blockIdx.x] = max |dO| over this workgroup's share of segment s, as float bits
@@ -108,7 +109,7 @@ __device__ __forceinline__ void split3(float x, uint32_t& w01, uint32_t& w23)
 // One row is handled by D/8 adjacent lanes (16 bytes of dO each).
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(
-    const uint16_t* __restrict__ o, const float* __restrict__ o_f32, const float* __restrict__ lse,
+    const uint16_t* __restrict__ o, const uint16_t* __restrict__ o_f16, const float* __restrict__ lse,
     const uint16_t* __restrict__ d_o, const int32_t* __restrict__ q_idx, const uint32_t* __restrict__ amax_partial,
     int n_partial, int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
     uint16_t* __restrict__ aux_perm, float* __restrict__ inv_scale_out)
@@ -142,10 +143,11 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
             gs[2 * w] = __uint_as_float(gw[w] << 16) * scale;
             gs[2 * w + 1] = __uint_as_float(gw[w] & 0xffff0000u) * scale;
         }
-        if (o_f32) {   // full-precision copy of O kept by the forward
-            const float4 y0 = *reinterpret_cast<const float4*>(o_f32 + (seg + src) * D + c8 * 8);
-            const float4 y1 = *reinterpret_cast<const float4*>(o_f32 + (seg + src) * D + c8 * 8 + 4);
-            y[0] = y0.x; y[1] = y0.y; y[2] = y0.z; y[3] = y0.w; y[4] = y1.x; y[5] = y1.y; y[6] = y1.z; y[7] = y1.w;
+        if (o_f16) {   // fp16 copy of O kept by the forward (three more significant bits than bf16)
+            const uint4 yh = *reinterpret_cast<const uint4*>(o_f16 + (seg + src) * D + c8 * 8);
+            const f16x8h yv = __builtin_bit_cast(f16x8h, yh);
+#pragma unroll
+            for (int w = 0; w < 8; ++w) y[w] = (float)yv[w];
         } else {
             const uint4 yb = *reinterpret_cast<const uint4*>(o + (seg + src) * D + c8 * 8);
             const uint32_t yw[4] = {yb.x, yb.y, yb.z, yb.w};
@@ -180,7 +182,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     }
 }
 
-int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, const void* d_o, const int32_t* q_idx,
+int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const int32_t* q_idx,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st)
 {
@@ -192,10 +194,10 @@ int launch_bwd_prep_bf16(const void* o, const float* o_f32, const float* lse, co
     const long long threads = (long long)T * (d / 8);
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
     if (d == 64)
-        hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
+        hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
                            q_idx, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else if (d == 128)
-        hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, o_f32, lse, (const uint16_t*)d_o,
+        hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
                            q_idx, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else
         return SCFA_EUNSUPPORTED;

@@ -13,9 +13,9 @@
 // transposing LDS reads.
 //
 // K / V tiles and the key positions travel global memory -> LDS asynchronously (no
-// registers, no LDS stores), FWD_PREFETCH tiles ahead of the one being computed, into a ring
-// of FWD_PREFETCH + 1 swizzled buffers; one workgroup barrier per tile both publishes the
-// tile that has landed and retires the buffer that is refilled next.
+// registers, no LDS stores), NBUF - 1 tiles ahead of the one being computed, into a ring of
+// NBUF swizzled buffers; one workgroup barrier per tile both publishes the tile that has
+// landed and retires the buffer that is refilled next.
 //
 // The permuted queries arrive multiplied by tau * log2(e), so the contraction yields the
 // scores in base-2 units, x = tau * log2(e) * <q, k>, and no scaling is left per element.
@@ -53,7 +53,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
     const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
-    uint16_t* __restrict__ o, float* __restrict__ lse, float* __restrict__ o_f32)
+    uint16_t* __restrict__ o, float* __restrict__ lse, uint16_t* __restrict__ o_f16)
 {
     static_assert(NW * QB * 32 == FWD_TILE_M, "workgroup must cover the forward query tile");
     (void)tau;   // already folded into the permuted queries
@@ -293,7 +293,13 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                     pk.x = (uint32_t)__builtin_bit_cast(uint16_t, y0) | ((uint32_t)__builtin_bit_cast(uint16_t, y1) << 16);
                     pk.y = (uint32_t)__builtin_bit_cast(uint16_t, y2) | ((uint32_t)__builtin_bit_cast(uint16_t, y3) << 16);
                     *reinterpret_cast<uint2*>(o + row + db * 32 + 8 * g) = pk;
-                    if (o_f32) *reinterpret_cast<float4*>(o_f32 + row + db * 32 + 8 * g) = make_float4(x0, x1, x2, x3);
+                    if (o_f16) {   // the same values with 11 significant bits, for the backward's D = <dO, O>
+                        const _Float16 z0 = (_Float16)x0, z1 = (_Float16)x1, z2 = (_Float16)x2, z3 = (_Float16)x3;
+                        uint2 hk;
+                        hk.x = (uint32_t)__builtin_bit_cast(uint16_t, z0) | ((uint32_t)__builtin_bit_cast(uint16_t, z1) << 16);
+                        hk.y = (uint32_t)__builtin_bit_cast(uint16_t, z2) | ((uint32_t)__builtin_bit_cast(uint16_t, z3) << 16);
+                        *reinterpret_cast<uint2*>(o_f16 + row + db * 32 + 8 * g) = hk;
+                    }
                 }
             if (h == 0) lse[seg + qpos[b]] = ltot > 0.f ? (m[b] + log2f(ltot)) * LN2 : -INFINITY;
         }
@@ -303,7 +309,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
 template <int D, int NW, int QB>
 static int launch_fwd_t(const void* q, const void* k, const void* v, const int32_t* q_idx, const int32_t* k_idx,
                         const int32_t* work, int n_work, int S, int T, float tau, int strict, void* o,
-                        float* lse, float* o_f32, hipStream_t st)
+                        float* lse, void* o_f16, hipStream_t st)
 {
     constexpr size_t smem = (size_t)FwdRing<D>::NBUF * FwdRing<D>::BUF_BYTES;
     static bool attr_set = false;
@@ -315,18 +321,18 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const int32
     dim3 grid((unsigned)((size_t)S * n_work));
     hipLaunchKernelGGL((attn_fwd_f16_kernel<D, NW, QB>), grid, dim3(NW * 64), smem, st, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, q_idx, k_idx, work, n_work, S, T, tau,
-                       strict, (uint16_t*)o, lse, o_f32);
+                       strict, (uint16_t*)o, lse, (uint16_t*)o_f16);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
 int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
                          const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
-                         float tau, int strict, void* o, float* lse, float* o_f32, hipStream_t st)
+                         float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st)
 {
     ProfScope prof(SCFA_K_FWD, st);
-    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f32, st);
-    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f32, st);
+    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
+    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
     return SCFA_EUNSUPPORTED;
 }
 

@@ -34,7 +34,7 @@ class Context:
     counters: Optional[torch.Tensor]
     o: Optional[torch.Tensor] = None
     lse: Optional[torch.Tensor] = None
-    o_f32: Optional[torch.Tensor] = None
+    o_f16: Optional[torch.Tensor] = None
     q_bucket_sorted: Optional[torch.Tensor] = None
     k_bucket_sorted: Optional[torch.Tensor] = None
     q_off: Optional[torch.Tensor] = None
@@ -45,12 +45,12 @@ def _seg(x):
     return x.reshape(x.shape[0] * x.shape[1], *x.shape[2:])
 
 
-def _o_f32_buffer(q, need_bwd):
-    """fp32 side copy of O for the backward's D = <dO, O> (bf16 path, training only).
+def _o_f16_buffer(q, need_bwd):
+    """fp16 side copy of O for the backward's D = <dO, O> (bf16 path, training only).
     Rows of dropped queries are never written and never read back."""
     if not need_bwd or q.dtype != torch.bfloat16:
         return None
-    return torch.empty(q.shape, dtype=torch.float32, device=q.device)
+    return torch.empty(q.shape, dtype=torch.float16, device=q.device)
 
 
 def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True, strict=False):
@@ -64,17 +64,17 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True, stric
                                        q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
                                                         want_bwd=need_bwd, flags=flags)
-    o_f32 = _o_f32_buffer(q, need_bwd)
-    o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f32_out=o_f32, flags=flags)
+    o_f16 = _o_f16_buffer(q, need_bwd)
+    o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f16_out=o_f16, flags=flags)
     ctx = Context(sc.SCFA_HASH, B, H, nb, sm_scale, flags, q_p, k_p, v_p, q_idx, k_idx, None, None, fwd_work, bwd_work,
-                  counters, o, lse, o_f32, q_bs, k_bs, q_off, k_off)
+                  counters, o, lse, o_f16, q_bs, k_bs, q_off, k_off)
     return o, lse, ctx
 
 
 def hash_backward(ctx: Context, d_o, ws=None, outs=None):
     """dQ, dK, dV (fp32, original order) of hash-sparse attention."""
     return sc.scfa_hash_attn_bwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_idx, ctx.k_idx, ctx.fwd_work, ctx.bwd_work,
-                                 ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale, ws=ws, outs=outs, o_f32=ctx.o_f32, flags=ctx.flags)
+                                 ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale, ws=ws, outs=outs, o_f16=ctx.o_f16, flags=ctx.flags)
 
 
 def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True, strict=False):
@@ -87,14 +87,14 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True, strict=Fals
                                        to_f16=q.dtype == torch.bfloat16, q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_QKDROP, q_idx, k_idx, n_q, n_k, 1, tiles,
                                                         want_bwd=need_bwd, flags=flags)
-    o_f32 = _o_f32_buffer(q, need_bwd)
-    o, lse = sc.scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_f32_out=o_f32, flags=flags)
+    o_f16 = _o_f16_buffer(q, need_bwd)
+    o, lse = sc.scfa_qkdrop_attn_fwd(q_c, k_c, v_c, q_idx, k_idx, n_q, fwd_work, B, H, sm_scale, o_f16_out=o_f16, flags=flags)
     ctx = Context(sc.SCFA_QKDROP, B, H, 1, sm_scale, flags, q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, fwd_work, bwd_work,
-                  counters, o, lse, o_f32)
+                  counters, o, lse, o_f16)
     return o, lse, ctx
 
 
 def qkdrop_backward(ctx: Context, d_o, ws=None, outs=None):
     return sc.scfa_qkdrop_attn_bwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_idx, ctx.k_idx, ctx.n_q, ctx.n_k,
                                    ctx.fwd_work, ctx.bwd_work, ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale,
-                                   ws=ws, outs=outs, o_f32=ctx.o_f32, flags=ctx.flags)
+                                   ws=ws, outs=outs, o_f16=ctx.o_f16, flags=ctx.flags)
