@@ -63,6 +63,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     constexpr int TILE_ELEMS = BN * D;
     constexpr int BUF_BYTES = FwdRing<D>::BUF_BYTES;  // K tile, V tile, key positions
     constexpr int LOADS_PER_TILE = 2 * AsyncTile<D, BN, THREADS>::ROUNDS + 1;   // per wavefront
+    constexpr int KPW = BN / NW;                      // key positions loaded per wavefront
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     auto k_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
     auto v_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 2); };
@@ -125,15 +126,15 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const u32x4 k_desc = make_desc(kbase, (uint32_t)k_count * D * 2);
     const u32x4 v_desc = make_desc(vbase, (uint32_t)k_count * D * 2);
     const u32x4 p_desc = make_desc(kib, (uint32_t)k_count * 4);
-    // every wavefront issues the same number of loads per tile (16 key positions each), so one
+    // every wavefront issues the same number of loads per tile (BN / NW key positions each), so one
     // vmcnt threshold serves all; tiles past the end read zeros into a buffer nobody uses
     auto issue = [&](int jt, int buf) {
         const uint32_t base = lds0 + (uint32_t)(buf * BUF_BYTES);
         loader.load(k_desc, jt * loader.TILE_BYTES, base);
         loader.load(v_desc, jt * loader.TILE_BYTES, base + TILE_ELEMS * 2);
-        if (lane < 16)
-            async_load4(p_desc, __builtin_amdgcn_readfirstlane(base + TILE_ELEMS * 4 + wave * 64), (wave * 16 + lane) * 4,
-                        jt * BN * 4);
+        if (lane < KPW)
+            async_load4(p_desc, __builtin_amdgcn_readfirstlane(base + TILE_ELEMS * 4 + wave * KPW * 4),
+                        (wave * KPW + lane) * 4, jt * BN * 4);
     };
 
     // lane-invariant offsets of the transposing V reads
@@ -261,9 +262,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     auto step = [&](int jt, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         wait_async<LOADS_PER_TILE * (NBUF - 2)>();
-        if (MASKED && lane < 16) {
-            const int key = jt * BN + wave * 16 + lane;
-            if (key >= k_count) kpos_tile(cur)[wave * 16 + lane] = INT32_MAX;   // never allowed
+        if (MASKED && lane < KPW) {
+            const int key = jt * BN + wave * KPW + lane;
+            if (key >= k_count) kpos_tile(cur)[wave * KPW + lane] = INT32_MAX;   // never allowed
         }
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
