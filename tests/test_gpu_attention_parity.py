@@ -88,6 +88,25 @@ def test_strict_causal_fp32_forward():
     _full_check(_strict(W.hash_uniform(77, 1, 2, 300, 64, 3, dtype="f32", passes="fwd")), backward=False)
 
 
+# --------------------------------------------------------------- seeded random shapes
+
+@pytest.mark.parametrize("seed", range(12))
+def test_seeded_random_shapes(seed):
+    """Shapes, sparsity, variant and mask form drawn from a seeded generator: ragged lengths, bucket
+    counts from 1 to 40 (more buckets than a tile has rows), keep rates from 5 % to 100 %."""
+    rng = np.random.default_rng(1000 + seed)
+    T = int(rng.integers(1, 2600))
+    d = int(rng.choice([64, 128]))
+    B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    strict = bool(rng.integers(0, 2))
+    if rng.integers(0, 2):
+        wl = W.hash_uniform(seed, B, H, T, d, int(rng.integers(1, 41)))
+    else:
+        wl = W.qkdrop_bernoulli(seed, B, H, T, d, float(rng.uniform(0.05, 1.0)), float(rng.uniform(0.05, 1.0)))
+    wl.meta["strict"] = strict
+    _full_check(wl)
+
+
 # --------------------------------------------------------------- degenerate cases
 
 def test_bucket_present_in_q_but_absent_in_k_gives_zero_rows():
