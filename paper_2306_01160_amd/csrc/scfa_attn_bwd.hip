@@ -213,13 +213,16 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
 //   P = 2^X, dS = P dP'
 //   dV^T += dO^T P,  dK^T += Q^T dS   (d x keys; Q^T, dO^T by transposing LDS reads)
 // ===========================================================================
+// LDS ring of the dK/dV kernel: Q tile, dO tile, aux rows (three fp16 pieces of LSE log2 e and of D
+// per query) and query positions per buffer, filled asynchronously NBUF - 1 tiles ahead
 template <int D>
-struct DkdvSmem {
+struct DkdvRing {
     static constexpr int BM = BWD_TILE_M;
-    uint16_t Qs[2][BM * D];
-    uint16_t Gs[2][BM * D];     // dO rows
-    uint16_t aux[2][BM * 8];    // per query: three fp16 pieces of LSE log2 e and of D
-    int32_t qpos[2][BM];
+    static constexpr int TILE_ELEMS = BM * D;
+    static constexpr int AUX_OFF = TILE_ELEMS * 4;            // byte offsets inside a buffer
+    static constexpr int QPOS_OFF = AUX_OFF + BM * 16;
+    static constexpr int BUF_BYTES = QPOS_OFF + BM * 4;
+    static constexpr int NBUF = D == 64 ? 3 : 2;
 };
 
 template <int D>
@@ -233,7 +236,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 {
     constexpr int BM = BWD_TILE_M;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    DkdvSmem<D>& sm = *reinterpret_cast<DkdvSmem<D>*>(smem_raw);
+    using Ring = DkdvRing<D>;
+    constexpr int NBUF = Ring::NBUF, BUF_BYTES = Ring::BUF_BYTES;
+    constexpr int RPW = BM / 4;                                               // aux rows / positions loaded per wavefront
+    constexpr int LOADS_PER_TILE = 2 * AsyncTile<D, BM, 256>::ROUNDS + 2;     // per wavefront
+    auto q_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
+    auto g_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + Ring::TILE_ELEMS * 2); };
+    auto aux_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + Ring::AUX_OFF); };
+    auto qpos_tile = [&](int buf) { return reinterpret_cast<const int32_t*>(smem_raw + buf * BUF_BYTES + Ring::QPOS_OFF); };
+    const uint32_t lds0 = lds_address(smem_raw);
 
     const int s = blockIdx.x % S;
     const int w = blockIdx.x / S;
@@ -282,41 +293,38 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const int n_tiles = (q_count + BM - 1) / BM;
     const int n_masked = min((q_masked + BM - 1) / BM, n_tiles);   // leading tiles that need the causal test
 
-    TileRegs<D, BM, 256> qt, gt;
-    const rsrc_t q_rsrc = make_rsrc(q + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
-    const rsrc_t g_rsrc = make_rsrc(do_perm + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
-    const rsrc_t a_rsrc = make_rsrc(aux_perm + (seg + q_begin) * 8, (uint32_t)q_count * 16);
-    const rsrc_t p_rsrc = make_rsrc(q_idx + seg + q_begin, (uint32_t)q_count * 4);
-    uint4 aux_reg = make_uint4(0u, 0u, 0u, 0u);
-    int qp_reg = 0, q_row = 0;
-    auto fetch = [&](int jt) {
-        qt.load(q_rsrc, jt * qt.TILE_BYTES);
-        gt.load(g_rsrc, jt * gt.TILE_BYTES);
-        if (tid < BM) {
-            aux_reg = buffer_load16(a_rsrc, tid * 16, jt * BM * 16);
-            qp_reg = buffer_load4(p_rsrc, tid * 4, jt * BM * 4);
-            q_row = jt * BM + tid;
-        }
-    };
-    // Rows past the end of the range read as zeros everywhere (Q, dO, aux): P = 1 there, but
-    // dO = 0 and dP' = 0 make their contributions to dV and dK vanish.
-    auto stash = [&](int buf) {
-        qt.store_swz(sm.Qs[buf]);
-        gt.store_swz(sm.Gs[buf]);
-        if (tid < BM) {
-            *reinterpret_cast<uint4*>(&sm.aux[buf][tid * 8]) = aux_reg;
-            sm.qpos[buf][tid] = q_row < q_count ? qp_reg : -1;
+    AsyncTile<D, BM, 256> loader;
+    loader.init();
+    const u32x4 q_desc = make_desc(q + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
+    const u32x4 g_desc = make_desc(do_perm + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
+    const u32x4 a_desc = make_desc(aux_perm + (seg + q_begin) * 8, (uint32_t)q_count * 16);
+    const u32x4 p_desc = make_desc(q_idx + seg + q_begin, (uint32_t)q_count * 4);
+    // Every wavefront issues the same number of loads per tile, so one vmcnt threshold serves all.
+    // Rows past the end of the range (and whole tiles past the end) land as zeros everywhere (Q, dO,
+    // aux, positions): P = 1 there, but dO = 0 and dP' = 0 make their contributions to dV and dK
+    // vanish, with or without the causal test.
+    auto issue = [&](int jt, int buf) {
+        const uint32_t base = lds0 + (uint32_t)(buf * BUF_BYTES);
+        loader.load(q_desc, jt * loader.TILE_BYTES, base);
+        loader.load(g_desc, jt * loader.TILE_BYTES, base + Ring::TILE_ELEMS * 2);
+        if (lane < RPW) {
+            async_load16(a_desc, __builtin_amdgcn_readfirstlane(base + Ring::AUX_OFF + wave * RPW * 16),
+                         (wave * RPW + lane) * 16, jt * BM * 16);
+            async_load4(p_desc, __builtin_amdgcn_readfirstlane(base + Ring::QPOS_OFF + wave * RPW * 4),
+                        (wave * RPW + lane) * 4, jt * BM * 4);
         }
     };
 
     auto tile = [&](int buf, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint16_t* Qt = sm.Qs[buf];
-        const uint16_t* Gt = sm.Gs[buf];
+        const uint16_t* Qt = q_tile(buf);
+        const uint16_t* Gt = g_tile(buf);
+        const uint16_t* At = aux_tile(buf);
+        const int32_t* qpos_t = qpos_tile(buf);
         f32x16 sacc[2], pacc[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
-            const f16x8 ax = as_f16x8(*reinterpret_cast<const uint4*>(&sm.aux[buf][(qb * 32 + l32) * 8]));
+            const f16x8 ax = as_f16x8(*reinterpret_cast<const uint4*>(&At[(qb * 32 + l32) * 8]));
             sacc[qb] = mfma16(ax, sub_lse, zero16());
             pacc[qb] = mfma16(ax, sub_delta, zero16());
         }
@@ -334,7 +342,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
             for (int g = 0; g < 4; ++g) {
                 int qpa[4] = {0, 0, 0, 0};
                 if (MASKED) {
-                    const int4 qp = *reinterpret_cast<const int4*>(&sm.qpos[buf][qb * 32 + 8 * g + 4 * h]);
+                    const int4 qp = *reinterpret_cast<const int4*>(&qpos_t[qb * 32 + 8 * g + 4 * h]);
                     qpa[0] = qp.x; qpa[1] = qp.y; qpa[2] = qp.z; qpa[3] = qp.w;
                 }
 #pragma unroll
@@ -360,22 +368,23 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         }
     };
 
-    if (n_tiles > 0) {
-        fetch(0);
-        stash(0);
-    }
-    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) issue(u, u);
+    // one step: wait for this wavefront's share of tile jt, barrier (everyone's share has landed and
+    // everyone has left tile jt - 1), refill that tile's buffer, compute
+    int cur = 0;
     auto step = [&](int jt, auto masked_tag) {
-        const int buf = jt & 1;
-        const bool more = jt + 1 < n_tiles;
-        if (more) fetch(jt + 1);
-        tile(buf, masked_tag);
-        if (more) stash(buf ^ 1);
-        __syncthreads();
+        wait_async<LOADS_PER_TILE * (NBUF - 2)>();
+        lds_barrier();
+        const int refill = cur == 0 ? NBUF - 1 : cur - 1;
+        issue(jt + NBUF - 1, refill);
+        tile(cur, masked_tag);
+        cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;
     for (; jt < n_masked; ++jt) step(jt, std::true_type{});
     for (; jt < n_tiles; ++jt) step(jt, std::false_type{});
+    wait_async<0>();   // nothing may still be landing in LDS when the wavefront ends
 
     if (kvalid) {
         const float us = inv_scale[s];
@@ -400,7 +409,7 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
                          const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S,
                          int T, int strict, float* dk, float* dv, hipStream_t st)
 {
-    const size_t smem = sizeof(DkdvSmem<D>);
+    const size_t smem = (size_t)DkdvRing<D>::NBUF * DkdvRing<D>::BUF_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_f16_kernel<D>),
@@ -434,12 +443,14 @@ int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const
 //   X^T = K Q'^T - LSE log2 e, dP'^T = V dO^T - D (keys x queries; the accumulators start
 //   from the per-lane constants), P^T = 2^X^T, dS^T = P^T dP'^T, dQ^T += K^T dS^T
 // ===========================================================================
+// LDS ring of the dQ kernel: K tile, V tile and key positions per buffer, filled asynchronously
+// NBUF - 1 tiles ahead (the forward kernel's scheme)
 template <int D>
-struct DqSmem {
+struct DqRing {
     static constexpr int BN = FWD_TILE_N;
-    uint16_t Ks[2][BN * D];
-    uint16_t Vs[2][BN * D];
-    int32_t kpos[2][BN];
+    static constexpr int TILE_ELEMS = BN * D;
+    static constexpr int BUF_BYTES = TILE_ELEMS * 4 + BN * 4;
+    static constexpr int NBUF = D == 64 ? 3 : 2;
 };
 
 template <int D>
@@ -452,7 +463,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
 {
     constexpr int BN = FWD_TILE_N;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
-    DqSmem<D>& sm = *reinterpret_cast<DqSmem<D>*>(smem_raw);
+    constexpr int NBUF = DqRing<D>::NBUF, BUF_BYTES = DqRing<D>::BUF_BYTES, TILE_ELEMS = DqRing<D>::TILE_ELEMS;
+    constexpr int KPW = BN / 4;                                               // key positions loaded per wavefront
+    constexpr int LOADS_PER_TILE = 2 * AsyncTile<D, BN, 256>::ROUNDS + 1;     // per wavefront
+    auto k_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
+    auto v_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 2); };
+    auto kpos_tile = [&](int buf) { return reinterpret_cast<int32_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 4); };
+    const uint32_t lds0 = lds_address(smem_raw);
 
     const int s = blockIdx.x % S;
     const int w = blockIdx.x / S;
@@ -495,29 +512,27 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = min(k_nomask / BN, n_tiles);
 
-    TileRegs<D, BN, 256> kt, vt;
-    const rsrc_t k_rsrc = make_rsrc(k + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
-    const rsrc_t v_rsrc = make_rsrc(v + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
-    const rsrc_t p_rsrc = make_rsrc(k_idx + seg + k_begin, (uint32_t)k_count * 4);
-    int kp_reg = 0, kp_row = 0;
-    auto fetch = [&](int jt) {
-        kt.load(k_rsrc, jt * kt.TILE_BYTES);
-        vt.load(v_rsrc, jt * vt.TILE_BYTES);
-        if (tid < BN) {
-            kp_reg = buffer_load4(p_rsrc, tid * 4, jt * BN * 4);
-            kp_row = jt * BN + tid;
-        }
-    };
-    auto stash = [&](int buf) {
-        kt.store_swz(sm.Ks[buf]);
-        vt.store_swz(sm.Vs[buf]);
-        if (tid < BN) sm.kpos[buf][tid] = kp_row < k_count ? kp_reg : INT32_MAX;   // keys past the end are never allowed
+    AsyncTile<D, BN, 256> loader;
+    loader.init();
+    const u32x4 k_desc = make_desc(k + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
+    const u32x4 v_desc = make_desc(v + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
+    const u32x4 p_desc = make_desc(k_idx + seg + k_begin, (uint32_t)k_count * 4);
+    // every wavefront issues the same number of loads per tile, so one vmcnt threshold serves all;
+    // tiles past the end read zeros into a buffer nobody uses
+    auto issue = [&](int jt, int buf) {
+        const uint32_t base = lds0 + (uint32_t)(buf * BUF_BYTES);
+        loader.load(k_desc, jt * loader.TILE_BYTES, base);
+        loader.load(v_desc, jt * loader.TILE_BYTES, base + TILE_ELEMS * 2);
+        if (lane < KPW)
+            async_load4(p_desc, __builtin_amdgcn_readfirstlane(base + TILE_ELEMS * 4 + wave * KPW * 4),
+                        (wave * KPW + lane) * 4, jt * BN * 4);
     };
 
     auto tile = [&](int buf, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
-        const uint16_t* Kt = sm.Ks[buf];
-        const uint16_t* Vt = sm.Vs[buf];
+        const uint16_t* Kt = k_tile(buf);
+        const uint16_t* Vt = v_tile(buf);
+        const int32_t* kpos_t = kpos_tile(buf);
         f32x16 sacc[2], pacc[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) { sacc[kb] = s_start; pacc[kb] = p_start; }
@@ -535,7 +550,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
             for (int g = 0; g < 4; ++g) {
                 int kpa[4] = {0, 0, 0, 0};
                 if (MASKED) {
-                    const int4 kp = *reinterpret_cast<const int4*>(&sm.kpos[buf][kb * 32 + 8 * g + 4 * h]);
+                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
                     kpa[0] = kp.x; kpa[1] = kp.y; kpa[2] = kp.z; kpa[3] = kp.w;
                 }
 #pragma unroll
@@ -558,22 +573,28 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         }
     };
 
-    if (n_tiles > 0) {
-        fetch(0);
-        stash(0);
-    }
-    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < NBUF - 1; ++u) issue(u, u);
+    // one step: wait for this wavefront's share of tile jt, mark keys past the end of a ragged
+    // tile (always a masked tile), barrier, refill the buffer everyone has just left, compute
+    int cur = 0;
     auto step = [&](int jt, auto masked_tag) {
-        const int buf = jt & 1;
-        const bool more = jt + 1 < n_tiles;
-        if (more) fetch(jt + 1);
-        tile(buf, masked_tag);
-        if (more) stash(buf ^ 1);
-        __syncthreads();
+        constexpr bool MASKED = decltype(masked_tag)::value;
+        wait_async<LOADS_PER_TILE * (NBUF - 2)>();
+        if (MASKED && lane < KPW) {
+            const int key = jt * BN + wave * KPW + lane;
+            if (key >= k_count) kpos_tile(cur)[wave * KPW + lane] = INT32_MAX;   // never allowed
+        }
+        lds_barrier();
+        const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
+        issue(jt + NBUF - 1, refill);
+        tile(cur, masked_tag);
+        cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;
     for (; jt < n_free; ++jt) step(jt, std::false_type{});
     for (; jt < n_tiles; ++jt) step(jt, std::true_type{});
+    wait_async<0>();   // nothing may still be landing in LDS when the wavefront ends
 
     if (qvalid) {
         const float sq = tau * inv_scale[s];
@@ -593,7 +614,7 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
                        const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S, int T,
                        float tau, int strict, float* dq, hipStream_t st)
 {
-    const size_t smem = sizeof(DqSmem<D>);
+    const size_t smem = (size_t)DqRing<D>::NBUF * DqRing<D>::BUF_BYTES;
     static bool attr_set = false;
     if (!attr_set) {
         SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_f16_kernel<D>),
