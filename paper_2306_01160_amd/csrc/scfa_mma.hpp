@@ -87,17 +87,11 @@ __device__ __forceinline__ f16x8 pack_chunk(const f32x16& p, int cc)
 }
 
 // ---------------------------------------------------------------------------
-// Row-major fp16 tiles in LDS.  STRIDE is the row stride in elements.
+// Row-major fp16 tiles in LDS.
 //   "rows" operand : contraction along the row (head dimension), one 16-byte read
 //   "trans" operand: contraction along the tile's rows; two transposing 8-byte reads
 //                    (ds_read_b64_tr_b16) give 4 + 4 consecutive tile rows per lane
 // ---------------------------------------------------------------------------
-template <int STRIDE>
-__device__ __forceinline__ f16x8 lds_rows(const uint16_t* tile, int row, int col)
-{
-    return as_f16x8(*reinterpret_cast<const uint4*>(tile + row * STRIDE + col));
-}
-
 // ds_read_b64_tr_b16 within a block of 16 lanes: lane i receives element i%4 of the four
 // 4-element rows addressed by lanes i/4, i/4+4, i/4+8, i/4+12 of its block.
 __device__ __forceinline__ uint2 lds_tr_read(const uint16_t* p)
@@ -107,38 +101,7 @@ __device__ __forceinline__ uint2 lds_tr_read(const uint16_t* p)
     return __builtin_bit_cast(uint2, r);
 }
 
-// A operand (32 x 16) = transpose of tile[r0 .. r0+16)[c0 .. c0+32): lane l gets column
-// c0 + l%32 and tile rows { r0 + 4h + 0..3, r0 + 8 + 4h + 0..3 } (h = l/32), the slot order
-// pack_chunk gives the B operand.
-template <int STRIDE>
-__device__ __forceinline__ f16x8 lds_trans(const uint16_t* tile, int r0, int c0, int lane)
-{
-    const int r = lane & 15, blk = (lane >> 4) & 1, h = lane >> 5;
-    const uint16_t* p = tile + (r0 + 4 * h + (r >> 2)) * STRIDE + c0 + 16 * blk + 4 * (r & 3);
-    const uint2 a = lds_tr_read(p);
-    const uint2 b = lds_tr_read(p + 8 * STRIDE);
-    return as_f16x8(make_uint4(a.x, a.y, b.x, b.y));
-}
-
-// ---------------------------------------------------------------------------
-// Buffer loads: the resource carries the byte range of the rows a workgroup may read,
-// so rows past the end come back as zeros without any predication, and the per-tile
-// offset is a scalar (no vector address arithmetic in the tile loop).
-using rsrc_t = __amdgpu_buffer_rsrc_t;
 using u32x4 = unsigned int __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ rsrc_t make_rsrc(const void* base, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
-}
-__device__ __forceinline__ uint4 buffer_load16(rsrc_t r, int voffset, int soffset)
-{
-    return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, voffset, soffset, 0));
-}
-__device__ __forceinline__ int buffer_load4(rsrc_t r, int voffset, int soffset)
-{
-    return __builtin_amdgcn_raw_buffer_load_b32(r, voffset, soffset, 0);
-}
 
 // ---------------------------------------------------------------------------
 // Swizzled tiles: row stride D (no padding).  LDS has 64 banks of 4 bytes; a 16-byte read
@@ -170,7 +133,9 @@ __device__ __forceinline__ f16x8 swz_rows(const uint16_t* tile, int row, int col
 }
 
 // element offsets of the two transposing reads of lane `lane` for the operand
-// transpose(tile[r0 .. r0+16)[c0 .. c0+32)) (see lds_trans); loop-invariant per lane
+// A = transpose(tile[r0 .. r0+16)[c0 .. c0+32)): lane l gets column c0 + l%32 and tile rows
+// { r0 + 4h + 0..3, r0 + 8 + 4h + 0..3 } (h = l/32), the slot order pack_chunk gives the B operand;
+// loop-invariant per lane
 template <int D>
 __device__ __forceinline__ void swz_trans_offsets(int r0, int c0, int lane, int& off_a, int& off_b)
 {
@@ -270,46 +235,6 @@ struct AsyncTile {
         for (int u = 0; u < ROUNDS; ++u)
             async_load16(desc, __builtin_amdgcn_readfirstlane(wave_base + (uint32_t)(u * THREADS * 16)), voff[u],
                          tile_byte_offset);
-    }
-};
-
-// Cooperative copy of ROWS contiguous rows x D fp16 (one tile) from global memory into
-// registers and on into an LDS tile.  Rows past the end of the resource read as zeros.
-template <int D, int ROWS, int THREADS>
-struct TileRegs {
-    static constexpr int CHUNKS = D / 8;                   // 16-byte chunks per row
-    static constexpr int ITEMS = ROWS * CHUNKS / THREADS;  // chunks per thread
-    static constexpr int TILE_BYTES = ROWS * D * 2;
-    static_assert(ROWS * CHUNKS % THREADS == 0, "tile must split evenly over the workgroup");
-    uint4 r[ITEMS];
-
-    // tile_byte_offset is wave-uniform
-    __device__ __forceinline__ void load(rsrc_t rsrc, int tile_byte_offset)
-    {
-#pragma unroll
-        for (int u = 0; u < ITEMS; ++u)
-            r[u] = buffer_load16(rsrc, (int)threadIdx.x * 16, tile_byte_offset + u * THREADS * 16);
-    }
-    // padded layout, row stride STRIDE
-    template <int STRIDE>
-    __device__ __forceinline__ void store(uint16_t* tile) const
-    {
-#pragma unroll
-        for (int u = 0; u < ITEMS; ++u) {
-            const int item = threadIdx.x + THREADS * u;
-            const int row = item / CHUNKS, c8 = item % CHUNKS;
-            *reinterpret_cast<uint4*>(tile + row * STRIDE + c8 * 8) = r[u];
-        }
-    }
-    // swizzled layout, row stride D
-    __device__ __forceinline__ void store_swz(uint16_t* tile) const
-    {
-#pragma unroll
-        for (int u = 0; u < ITEMS; ++u) {
-            const int item = threadIdx.x + THREADS * u;
-            const int row = item / CHUNKS, c8 = item % CHUNKS;
-            *reinterpret_cast<uint4*>(tile + swz_offset<D>(row, c8 * 8)) = r[u];
-        }
     }
 };
 
