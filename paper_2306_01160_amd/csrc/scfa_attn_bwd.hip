@@ -292,6 +292,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 
     const int n_tiles = (q_count + BM - 1) / BM;
     const int n_masked = min((q_masked + BM - 1) / BM, n_tiles);   // leading tiles that need the causal test
+    int kmin_wave = kcmp;            // smallest position a query must have to see any key of this wavefront
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) kmin_wave = min(kmin_wave, __shfl_xor(kmin_wave, off));
+    kmin_wave = __builtin_amdgcn_readfirstlane(kmin_wave);
 
     AsyncTile<D, BM, 256> loader;
     loader.init();
@@ -374,11 +378,19 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     // everyone has left tile jt - 1), refill that tile's buffer, compute
     int cur = 0;
     auto step = [&](int jt, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         wait_async<LOADS_PER_TILE * (NBUF - 2)>();
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;
         issue(jt + NBUF - 1, refill);
-        tile(cur, masked_tag);
+        // positions ascend along the queries of an item: a tile whose last query lies before every
+        // key of this wavefront contributes nothing to it
+        bool skip = false;
+        if (MASKED) {
+            const int last = min(BM, q_count - jt * BM) - 1;
+            skip = kmin_wave > __builtin_amdgcn_readfirstlane(qpos_tile(cur)[last]);
+        }
+        if (!skip) tile(cur, masked_tag);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;
@@ -511,6 +523,10 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
 
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = min(k_nomask / BN, n_tiles);
+    int qmax_wave = qcmp;            // largest position any query of this wavefront may attend to
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) qmax_wave = max(qmax_wave, __shfl_xor(qmax_wave, off));
+    qmax_wave = __builtin_amdgcn_readfirstlane(qmax_wave);
 
     AsyncTile<D, BN, 256> loader;
     loader.init();
@@ -588,7 +604,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
         issue(jt + NBUF - 1, refill);
-        tile(cur, masked_tag);
+        // positions ascend along the keys of an item: a tile whose first key lies after every query
+        // of this wavefront contributes nothing to it
+        bool skip = false;
+        if (MASKED) skip = __builtin_amdgcn_readfirstlane(kpos_tile(cur)[0]) > qmax_wave;
+        if (!skip) tile(cur, masked_tag);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;

@@ -115,6 +115,13 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         m[b] = -INFINITY; thr[b] = -INFINITY; lsum[b] = 0.f;   // the first finite score always raises
     }
 
+    int qmax_wave = qcmp[0];         // largest position any query of this wavefront may attend to
+#pragma unroll
+    for (int b = 1; b < QB; ++b) qmax_wave = max(qmax_wave, qcmp[b]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) qmax_wave = max(qmax_wave, __shfl_xor(qmax_wave, off));
+    qmax_wave = __builtin_amdgcn_readfirstlane(qmax_wave);
+
     const uint16_t* kbase = k + (seg + k_begin) * D;
     const uint16_t* vbase = v + (seg + k_begin) * D;
     const int32_t* kib = k_idx + seg + k_begin;
@@ -269,7 +276,11 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
         issue(jt + NBUF - 1, refill);
-        tile(cur, masked_tag);
+        // positions ascend along the keys of an item: a tile whose first key lies after every query
+        // of this wavefront contributes nothing to it
+        bool skip = false;
+        if (MASKED) skip = __builtin_amdgcn_readfirstlane(kpos_tile(cur)[0]) > qmax_wave;
+        if (!skip) tile(cur, masked_tag);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;
