@@ -151,30 +151,41 @@ def cpu_baseline(wl, n_seg):
 def sweep(kind, steps):
     """Step time of the whole path against sparsity and sequence length, with the total number of
     tokens held fixed, on random inputs drawn on the device (the form of the paper's runtime-in-a-
-    vacuum study, Sec. 4.2 / 4.3: buckets and drops given for free, uniformly random).  Speed-ups are
-    over the same code with one bucket / nothing dropped (dense causal) at the same T."""
+    vacuum study, Sec. 4.2 / 4.3 and App. C: buckets and drops given for free, uniformly random;
+    plus hash rows with bucket sizes skewed like 1 / rank, since real hash buckets are uneven).
+    Speed-ups are over the same code with one bucket / nothing dropped (dense causal) at the same T.
+    Every row also splits the kernel time into pre-processing (sort or compaction, gather,
+    schedule), forward, and backward (pre-pass, dK/dV, dQ)."""
     import torch
     from paper_2306_01160_amd import binding as sc
     dev = torch.device("cuda:0")
     g = torch.Generator(device=dev); g.manual_seed(1234)
     rows = []
     if kind == "hash":
-        d, H, tokens = 64, 12, 24 * 16384
-        grid = [(T, nb) for T in (4096, 8192, 16384, 32768) for nb in (1, 2, 4, 8, 16, 32, 64)]
+        d, heads, tokens = 64, 12, 24 * 16384
+        grid = [(T, nb, "uniform") for T in (1024, 2048, 4096, 8192, 16384, 32768, 65536) for nb in (1, 2, 4, 8, 16, 32, 64)]
+        grid += [(T, nb, "zipf") for T in (16384,) for nb in (4, 8, 16, 64)]
     else:
-        d, H, tokens = 128, 16, 16 * 32768
-        grid = [(T, r) for T in (8192, 16384, 32768) for r in (1.0, 0.7, 0.5, 0.3, 0.1)]
+        d, heads, tokens = 128, 16, 16 * 32768
+        grid = [(T, r, "bernoulli") for T in (8192, 16384, 32768) for r in (1.0, 0.7, 0.5, 0.3, 0.1)]
     tau = 1.0 / float(np.sqrt(d))
     cache = {}
-    for T, par in grid:
-        B = tokens // (H * T)
+    for T, par, dist in grid:
+        S = tokens // T
+        H = min(heads, S)
+        B = S // H
         if T not in cache:
             cache.clear()
             cache[T] = tuple((torch.randn((B, H, T, d), device=dev, generator=g) * 0.5).to(torch.bfloat16) for _ in range(4))
         q, k, v, do = cache[T]
         if kind == "hash":
-            lq = torch.randint(0, par, (B, H, T), device=dev, generator=g, dtype=torch.int32)
-            lk = torch.randint(0, par, (B, H, T), device=dev, generator=g, dtype=torch.int32)
+            if dist == "zipf":     # bucket b drawn with probability proportional to 1 / (b + 1), queries and keys alike
+                pr = (1.0 / torch.arange(1, par + 1, device=dev, dtype=torch.float32)).expand(B * H, par)
+                lq = torch.multinomial(pr, T, replacement=True, generator=g).to(torch.int32).reshape(B, H, T)
+                lk = torch.multinomial(pr, T, replacement=True, generator=g).to(torch.int32).reshape(B, H, T)
+            else:
+                lq = torch.randint(0, par, (B, H, T), device=dev, generator=g, dtype=torch.int32)
+                lk = torch.randint(0, par, (B, H, T), device=dev, generator=g, dtype=torch.int32)
             job = HashJob(tensors=(q, k, v, do, lq, lk), nb=par, tau=tau)
         else:
             lq = (torch.rand((B, H, T), device=dev, generator=g) < par).to(torch.uint8)
@@ -182,18 +193,27 @@ def sweep(kind, steps):
             job = HashJob(tensors=(q, k, v, do, lq, lk), nb=None, tau=tau)
         ms = job.timed(steps, 2)
         kt = job.kernel_times(3)
-        attn = sum(kt[x]["ms_per_step"] for x in ("fwd", "bwd_dkdv", "bwd_dq"))
+        part = lambda names: sum(kt[x]["ms_per_step"] for x in names if x in kt)
+        attn = part(("fwd", "bwd_dkdv", "bwd_dq"))
         cnt = job.ctx.counters.cpu().numpy().sum(0)
         fm, fn, bn, bm = sc.scfa_tile_config(d, sc.SCFA_BF16)
         tile_flops = int(cnt[0]) * fm * fn * 6 * d + int(cnt[2]) * bm * bn * 8 * d
-        rows.append({"T": T, "B": B, "H": H, "d": d, ("nb" if kind == "hash" else "keep"): par, "ms_per_step": ms,
-                     "attn_kernels_ms": attn, "computed_tile_tflops_kernels": tile_flops / (attn * 1e-3) / 1e12})
-        log(f"[sweep] T={T} {par}: {ms:.3f} ms/step, attention kernels {attn:.3f} ms")
+        rows.append({"T": T, "B": B, "H": H, "d": d, ("nb" if kind == "hash" else "keep"): par, "labels": dist,
+                     "ms_per_step": ms, "attn_kernels_ms": attn, "preprocess_ms": part(("sort", "compact", "gather", "ranges")),
+                     "fwd_ms": part(("fwd",)), "bwd_ms": part(("bwd_prep", "bwd_dkdv", "bwd_dq")),
+                     "computed_tile_area_vs_dense": None,
+                     "computed_tile_tflops_kernels": tile_flops / (attn * 1e-3) / 1e12, "_tile_flops": tile_flops})
+        log(f"[sweep] T={T} {par} {dist}: {ms:.3f} ms/step, attention kernels {attn:.3f} ms")
         del job
     dense = {r["T"]: r for r in rows if r.get("nb") == 1 or r.get("keep") == 1.0}
     for r in rows:
         r["speedup_end_to_end"] = dense[r["T"]]["ms_per_step"] / r["ms_per_step"]
         r["speedup_kernels"] = dense[r["T"]]["attn_kernels_ms"] / r["attn_kernels_ms"]
+        r["speedup_fwd"] = dense[r["T"]]["fwd_ms"] / r["fwd_ms"]
+        r["speedup_bwd"] = dense[r["T"]]["bwd_ms"] / r["bwd_ms"]
+        r["computed_tile_area_vs_dense"] = r["_tile_flops"] / dense[r["T"]]["_tile_flops"]
+    for r in rows:
+        del r["_tile_flops"]
     print(json.dumps({"sweep": kind, "tokens_per_step": tokens, "dtype": "bf16", "data": "synthetic", "steps": steps,
                       "rows": rows}), flush=True)
 

@@ -219,3 +219,18 @@ def test_config5_qkdrop_T32768_d128_sampled():
     dq = grads[0].cpu().numpy()
     assert not dq[wl.lab_q == 0].any()
     assert not o.float().cpu().numpy()[wl.lab_q == 0].any()
+
+
+def test_hash_T65536_sampled():
+    """The longest sequence of the speed-up sweep (B=1, H=2, T=65536, d=64, 16 uniformly random
+    buckets): sampled rows of one head; the schedule's index vector no longer fits in LDS here."""
+    T = 65536
+    wl = W.hash_uniform(65, 1, 2, T, 64, 16)
+    o, lse, grads, _ = run_gpu(wl)
+    rows = np.unique(np.concatenate([np.arange(0, 140), np.arange(40000, 40100), np.arange(T - 140, T),
+                                     np.random.default_rng(2).integers(0, T, 100)])).astype(np.int32)
+    segs = [1]
+    errs = compare_forward(wl, o, lse, segs=segs, rows=rows)
+    errs.update(compare_backward(wl, grads, segs=segs, q_rows=rows, k_rows=rows))
+    print(wl.name, errs)
+    assert_within(errs, wl.dtype)
