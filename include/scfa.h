@@ -61,6 +61,7 @@ extern "C" {
 #define SCFA_FLAG_STRICT_CAUSAL 1   /* allowed keys are at strictly earlier positions */
 
 #define SCFA_MAX_BUCKETS 256
+#define SCFA_MAX_T 16777200     /* positions take the low 24 bits of a sort key */
 #define SCFA_WORK_STRIDE 8      /* int32 words per work item */
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -85,20 +86,25 @@ const char *scfa_error_string(int code);
  *                      (bucket[idx[r]], idx[r]) is lexicographically increasing
  *   bucket_sorted_out  [S,T] int32 (nullable): bucket id of sorted row r
  *   bucket_off_out     [S,nb+1] int32: off[s,b] = number of tokens with id < b
+ *   sort_key_out       [S,T] uint32 (nullable; needs T <= SCFA_MAX_T): the pair the rows
+ *                      are ordered by, packed as bucket << 24 | position; increasing
+ *                      along r.  The hash-sparse attention entry points take these: "same
+ *                      bucket and position <= p" is one range test on them.
  * Limits: 1 <= nb <= SCFA_MAX_BUCKETS, 1 <= T, 1 <= S.
  */
 int scfa_sort_by_bucket(const int32_t *bucket, int S, int T, int nb,
                         int32_t *idx_out, int32_t *bucket_sorted_out,
-                        int32_t *bucket_off_out, void *stream);
+                        int32_t *bucket_off_out, uint32_t *sort_key_out, void *stream);
 
 /* The same sort for the query and the key bucket ids of one attention call in ONE
  * launch (Sec. 3.2 sorts both); outputs as above, one set per side.  The *_sorted_out
- * pointers are nullable. */
+ * and *_sort_key_out pointers are nullable. */
 int scfa_sort_by_bucket_pair(const int32_t *bucket_q, const int32_t *bucket_k,
                              int S, int T, int nb,
                              int32_t *q_idx_out, int32_t *q_sorted_out, int32_t *q_off_out,
+                             uint32_t *q_sort_key_out,
                              int32_t *k_idx_out, int32_t *k_sorted_out, int32_t *k_off_out,
-                             void *stream);
+                             uint32_t *k_sort_key_out, void *stream);
 
 /* ------------------------------------------------------------------------
  * a0. LSH bucketing, the step in front of the hash-sparse path (Sec. 4.2 "Hashing
@@ -172,9 +178,13 @@ int scfa_gather_qkv(const void *q, const void *k, const void *v,
  * a4. Tile-skip schedule.  The paper finds, per block of queries, the range of
  * key blocks that can hold an allowed pair (Sec. 3.1 j_stop; Sec. 3.2 j_start,
  * j_stop and its causal refinement).  This library owns its tiling, so it
- * anchors tiles at bucket boundaries: every work item covers query rows of ONE
+ * anchors tiles at bucket boundaries: a work item covers query rows of ONE
  * bucket and the keys of that same bucket, so the bucket test is structural
  * and only the causal test on original positions remains inside a tile.
+ * Buckets with fewer rows than a tile are the exception: consecutive ones are
+ * put together into one item (as many whole buckets as fit a tile of the
+ * tiled side) that spans all their queries and all their keys; inside such an
+ * item every tile takes the bucket and the causal test.
  *
  * Tile sizes must be the ones scfa_tile_config() reports for (d, dtype).
  *
@@ -184,19 +194,22 @@ int scfa_gather_qkv(const void *q, const void *k, const void *v,
  *   q_idx,k_idx [S,T] original positions of the permuted rows
  *
  *   fwd_work_out [S, n_fwd, 8] int32, n_fwd = scfa_num_work_items(T, nb, fwd_tile_m).
- *     Item = { q_begin, q_count, k_begin, k_count, k_nomask, bucket, 0, 0 }:
+ *     Item = { q_begin, q_count, k_begin, k_count, k_nomask, bucket, n_buckets, 0 }:
  *     permuted query rows [q_begin, q_begin+q_count) attend permuted key rows
  *     [k_begin, k_begin+k_count): the keys of the same bucket whose position is
  *     <= the LARGEST query position of the item.  The first k_nomask of these
  *     keys have a position <= the SMALLEST query position: no mask needed.
+ *     n_buckets > 1: all rows of buckets [bucket, bucket + n_buckets) on both
+ *     sides, k_nomask = 0.
  *     Items of a segment are ordered by bucket pair (bucket / 2) and, inside a pair,
  *     by decreasing k_count; unused trailing items have q_count == 0.
  *   bwd_work_out [S, n_bwd, 8] int32 (nullable), n_bwd = scfa_num_work_items(T, nb, bwd_tile_n).
- *     Item = { k_begin, k_count, q_begin, q_count, q_masked, bucket, 0, 0 }:
+ *     Item = { k_begin, k_count, q_begin, q_count, q_masked, bucket, n_buckets, 0 }:
  *     permuted key rows [k_begin, k_begin+k_count) are attended by permuted
  *     query rows [q_begin, q_begin+q_count): the queries of the same bucket
  *     whose position is >= the SMALLEST key position of the item.  Only the
  *     first q_masked of them (position < the LARGEST key position) need a mask.
+ *     n_buckets > 1: all rows of those buckets on both sides, q_masked = q_count.
  *     Ordered by bucket pair and, inside a pair, by decreasing q_count.
  *   counters_out [S,4] int64 (nullable): { forward tiles of fwd_tile_m x fwd_tile_n,
  *     sum of q_count*k_count, backward tiles of bwd_tile_m x bwd_tile_n, sum of
@@ -221,8 +234,8 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
 
 /* ------------------------------------------------------------------------
  * a5 (+a8). Forward attention over the scheduled tiles (Sec. 3.1 / 3.2; the
- * per-tile work of Alg. 1 / Alg. 2: scores, causal mask on original positions,
- * online softmax with the NaN-safe handling of fully masked rows, P.V).
+ * per-tile work of Alg. 1 / Alg. 2: scores, bucket and causal mask, online softmax
+ * with the NaN-safe handling of fully masked rows, P.V).
  *
  *   q_perm,k_perm,v_perm  [S,T,d] rows in sorted (hash) or compacted (qkdrop) order, as
  *                         scfa_gather_rows writes them: fp32 for SCFA_F32, fp16
@@ -231,7 +244,10 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  *                         take <q_perm, k_perm> as the exponent in base 2 and apply no
  *                         scaling of their own (one rounding of q * tau * log2 e to the
  *                         compute format: relative 2^-12 per element for fp16)
- *   q_idx,k_idx           [S,T] original positions of those rows
+ *   q_sort_key,k_sort_key [S,T] sort keys of those rows (scfa_sort_by_bucket's sort_key_out);
+ *                         the QK-dropping entry points take the compacted index vectors
+ *                         q_idx, k_idx themselves (one bucket, id 0: position = sort key)
+ *   T                     at most SCFA_MAX_T
  *   fwd_work, n_fwd       work list of scfa_block_ranges
  *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d)); the same value
  *                         the queries were gathered with
@@ -249,7 +265,7 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  * writes zeros / -inf for the dropped query rows idx[n_q[s] .. T).
  */
 int scfa_hash_attn_fwd(const void *q_perm, const void *k_perm, const void *v_perm,
-                       const int32_t *q_idx, const int32_t *k_idx,
+                       const uint32_t *q_sort_key, const uint32_t *k_sort_key,
                        const int32_t *fwd_work, int n_fwd,
                        int B, int H, int T, int d, int dtype, float sm_scale, int flags,
                        void *o_out, float *lse_out, void *o_f16_out, void *stream);
@@ -286,7 +302,7 @@ int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
 size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype);
 
 int scfa_hash_attn_bwd(const void *q_perm, const void *k_perm, const void *v_perm,
-                       const int32_t *q_idx, const int32_t *k_idx,
+                       const uint32_t *q_sort_key, const uint32_t *k_sort_key,
                        const int32_t *fwd_work, int n_fwd,
                        const int32_t *bwd_work, int n_bwd,
                        const void *o, const void *o_f16, const float *lse, const void *d_o,

@@ -53,10 +53,10 @@ def lib():
         L.scfa_last_hip_error.restype = ci
         L.scfa_error_string.restype = ctypes.c_char_p
         L.scfa_error_string.argtypes = [ci]
-        L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp]
+        L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp]
         L.scfa_lsh_buckets.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
-        L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp]
+        L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.scfa_compact_keep_pair.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
         L.scfa_gather_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
         L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp]
@@ -143,15 +143,17 @@ def scfa_lsh_buckets(x_q: torch.Tensor, x_k, R: torch.Tensor, H: int, nb: int):
     return (out[0], out[1]) if x_k is not None else out[0]
 
 
-def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int):
-    """bucket [S,T] int32 -> idx [S,T], bucket_sorted [S,T], off [S,nb+1] (all int32)."""
+def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int, want_sort_key=False):
+    """bucket [S,T] int32 -> idx [S,T], bucket_sorted [S,T], off [S,nb+1] (all int32); with
+    want_sort_key also the [S,T] sort keys bucket << 24 | position (uint32 bits in an int32 tensor)."""
     S, T = bucket.shape
     idx = torch.empty_like(bucket)
     bsorted = torch.empty_like(bucket)
     off = torch.empty((S, nb + 1), dtype=torch.int32, device=bucket.device)
-    _check(lib().scfa_sort_by_bucket(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _stream()),
+    key = torch.empty_like(bucket) if want_sort_key else None
+    _check(lib().scfa_sort_by_bucket(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _ptr(key), _stream()),
            "scfa_sort_by_bucket")
-    return idx, bsorted, off
+    return (idx, bsorted, off, key) if want_sort_key else (idx, bsorted, off)
 
 
 def scfa_compact_keep(keep: torch.Tensor):
@@ -164,17 +166,21 @@ def scfa_compact_keep(keep: torch.Tensor):
 
 
 def scfa_sort_by_bucket_pair(bucket_q: torch.Tensor, bucket_k: torch.Tensor, nb: int, want_sorted=True):
-    """Both sides of one attention call in one launch -> (q_idx, q_sorted, q_off), (k_idx, k_sorted, k_off)."""
+    """Both sides of one attention call in one launch ->
+    (q_idx, q_sorted, q_off, q_sort_key), (k_idx, k_sorted, k_off, k_sort_key)."""
     S, T = bucket_q.shape
     assert bucket_k.shape == bucket_q.shape
     both = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device)
     srt = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device) if want_sorted else None
     off = torch.empty((2, S, nb + 1), dtype=torch.int32, device=bucket_q.device)
+    key = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device)
     _check(lib().scfa_sort_by_bucket_pair(_ptr(bucket_q), _ptr(bucket_k), S, T, nb, _ptr(both[0]),
-                                          _ptr(srt[0]) if want_sorted else None, _ptr(off[0]), _ptr(both[1]),
-                                          _ptr(srt[1]) if want_sorted else None, _ptr(off[1]), _stream()),
+                                          _ptr(srt[0]) if want_sorted else None, _ptr(off[0]), _ptr(key[0]),
+                                          _ptr(both[1]), _ptr(srt[1]) if want_sorted else None, _ptr(off[1]),
+                                          _ptr(key[1]), _stream()),
            "scfa_sort_by_bucket_pair")
-    return (both[0], srt[0] if want_sorted else None, off[0]), (both[1], srt[1] if want_sorted else None, off[1])
+    return ((both[0], srt[0] if want_sorted else None, off[0], key[0]),
+            (both[1], srt[1] if want_sorted else None, off[1], key[1]))
 
 
 def scfa_compact_keep_pair(keep_q: torch.Tensor, keep_k: torch.Tensor):
@@ -233,13 +239,13 @@ def scfa_block_ranges(variant, q_idx, k_idx, q_off, k_off, nb, tiles, want_bwd=T
     return fwd, bwd, cnt
 
 
-def scfa_hash_attn_fwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, B, H, sm_scale, o_out=None, lse_out=None,
+def scfa_hash_attn_fwd(q_perm, k_perm, v_perm, q_sort_key, k_sort_key, fwd_work, B, H, sm_scale, o_out=None, lse_out=None,
                        o_f16_out=None, flags=0):
     S, T, d = q_perm.shape
     assert S == B * H
     o = torch.empty((B, H, T, d), dtype=_out_dtype(q_perm), device=q_perm.device) if o_out is None else o_out
     lse = torch.empty((B, H, T), dtype=torch.float32, device=q_perm.device) if lse_out is None else lse_out
-    _check(lib().scfa_hash_attn_fwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
+    _check(lib().scfa_hash_attn_fwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_sort_key), _ptr(k_sort_key),
                                     _ptr(fwd_work), fwd_work.shape[1], B, H, T, d, dtype_code(q_perm),
                                     float(sm_scale), int(flags), _ptr(o), _ptr(lse), _ptr(o_f16_out), _stream()),
            "scfa_hash_attn_fwd")
@@ -269,7 +275,7 @@ def _bwd_outputs(B, H, T, d, dev, outs):
     return tuple(torch.empty((B, H, T, d), dtype=torch.float32, device=dev) for _ in range(3))
 
 
-def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, bwd_work, o, lse, d_o, B, H, sm_scale,
+def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_sort_key, k_sort_key, fwd_work, bwd_work, o, lse, d_o, B, H, sm_scale,
                        ws=None, outs=None, o_f16=None, flags=0):
     S, T, d = q_perm.shape
     dt = dtype_code(q_perm)
@@ -277,7 +283,7 @@ def scfa_hash_attn_bwd(q_perm, k_perm, v_perm, q_idx, k_idx, fwd_work, bwd_work,
     if ws is None:
         ws = torch.empty((need,), dtype=torch.uint8, device=q_perm.device)
     dq, dk, dv = _bwd_outputs(B, H, T, d, q_perm.device, outs)
-    _check(lib().scfa_hash_attn_bwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_idx), _ptr(k_idx),
+    _check(lib().scfa_hash_attn_bwd(_ptr(q_perm), _ptr(k_perm), _ptr(v_perm), _ptr(q_sort_key), _ptr(k_sort_key),
                                     _ptr(fwd_work), fwd_work.shape[1], _ptr(bwd_work), bwd_work.shape[1],
                                     _ptr(o), _ptr(o_f16), _ptr(lse), _ptr(d_o), B, H, T, d, dt, float(sm_scale),
                                     int(flags), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(ws), ws.numel(), _stream()),

@@ -55,12 +55,13 @@ ProfScope::~ProfScope()
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-static int check_attn_common(const void* q, const void* k, const void* v, const int32_t* q_idx,
-                             const int32_t* k_idx, const int32_t* work, int n_work, int B, int H, int T,
+static int check_attn_common(const void* q, const void* k, const void* v, const uint32_t* q_key,
+                             const uint32_t* k_key, const int32_t* work, int n_work, int B, int H, int T,
                              int d, int dtype, float sm_scale, int flags)
 {
-    if (!q || !k || !v || !q_idx || !k_idx || !work) return SCFA_EINVAL;
+    if (!q || !k || !v || !q_key || !k_key || !work) return SCFA_EINVAL;
     if (B <= 0 || H <= 0 || T <= 0 || n_work <= 0) return SCFA_EINVAL;
+    if (T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;   // positions take the low 24 bits of a sort key
     if (!(sm_scale > 0.f) || !isfinite(sm_scale)) return SCFA_EINVAL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return SCFA_EINVAL;
     if ((flags & ~SCFA_FLAG_STRICT_CAUSAL) != 0) return SCFA_EUNSUPPORTED;
@@ -71,12 +72,12 @@ static int check_attn_common(const void* q, const void* k, const void* v, const 
     return SCFA_OK;
 }
 
-static int attn_fwd_impl(const void* q, const void* k, const void* v, const int32_t* q_idx,
-                         const int32_t* k_idx, const int32_t* n_q, bool qkdrop, const int32_t* work,
+static int attn_fwd_impl(const void* q, const void* k, const void* v, const uint32_t* q_key,
+                         const uint32_t* k_key, const int32_t* n_q, bool qkdrop, const int32_t* work,
                          int n_work, int B, int H, int T, int d, int dtype, float sm_scale, int flags,
                          void* o, float* lse, void* o_f16, hipStream_t st)
 {
-    int rc = check_attn_common(q, k, v, q_idx, k_idx, work, n_work, B, H, T, d, dtype, sm_scale, flags);
+    int rc = check_attn_common(q, k, v, q_key, k_key, work, n_work, B, H, T, d, dtype, sm_scale, flags);
     if (rc != SCFA_OK) return rc;
     if (!o || !lse || !aligned16(o)) return SCFA_EINVAL;
     if (qkdrop && !n_q) return SCFA_EINVAL;
@@ -84,24 +85,24 @@ static int attn_fwd_impl(const void* q, const void* k, const void* v, const int3
     const int S = B * H;
     const int esize = dtype == SCFA_BF16 ? 2 : 4;
     if (qkdrop) {
-        rc = launch_zero_rows(q_idx, n_q, S, T, d * esize, o, nullptr, lse, -INFINITY, st);
+        rc = launch_zero_rows(reinterpret_cast<const int32_t*>(q_key), n_q, S, T, d * esize, o, nullptr, lse, -INFINITY, st);
         if (rc != SCFA_OK) return rc;
     }
     if (dtype == SCFA_F32)
-        return launch_attn_fwd_f32((const float*)q, (const float*)k, (const float*)v, q_idx, k_idx, work,
+        return launch_attn_fwd_f32((const float*)q, (const float*)k, (const float*)v, q_key, k_key, work,
                                    n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, (float*)o, lse, st);
-    return launch_attn_fwd_bf16(q, k, v, q_idx, k_idx, work, n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, o,
+    return launch_attn_fwd_bf16(q, k, v, q_key, k_key, work, n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, o,
                                 lse, o_f16, st);
 }
 
-static int attn_bwd_impl(const void* q, const void* k, const void* v, const int32_t* q_idx,
-                         const int32_t* k_idx, const int32_t* n_q, const int32_t* n_k, bool qkdrop,
+static int attn_bwd_impl(const void* q, const void* k, const void* v, const uint32_t* q_key,
+                         const uint32_t* k_key, const int32_t* n_q, const int32_t* n_k, bool qkdrop,
                          const int32_t* fwd_work, int n_fwd, const int32_t* bwd_work, int n_bwd,
                          const void* o, const void* o_f16, const float* lse, const void* d_o, int B, int H,
                          int T, int d, int dtype, float sm_scale, int flags, float* dq, float* dk, float* dv,
                          void* ws, size_t ws_bytes, hipStream_t st)
 {
-    int rc = check_attn_common(q, k, v, q_idx, k_idx, fwd_work, n_fwd, B, H, T, d, dtype, sm_scale, flags);
+    int rc = check_attn_common(q, k, v, q_key, k_key, fwd_work, n_fwd, B, H, T, d, dtype, sm_scale, flags);
     if (rc != SCFA_OK) return rc;
     if (!bwd_work || n_bwd <= 0 || (!o && !o_f16) || !lse || !d_o || !dq || !dk || !dv || !ws) return SCFA_EINVAL;
     if (!aligned16(o) || !aligned16(o_f16) || !aligned16(d_o) || !aligned16(dq) || !aligned16(dk) || !aligned16(dv)) return SCFA_EINVAL;
@@ -126,17 +127,17 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const int3
     float* inv_scale = reinterpret_cast<float*>(w);
 
     if (qkdrop) {
-        rc = launch_zero_rows(q_idx, n_q, S, T, d * 4, dq, nullptr, nullptr, 0.f, st);
+        rc = launch_zero_rows(reinterpret_cast<const int32_t*>(q_key), n_q, S, T, d * 4, dq, nullptr, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
-        rc = launch_zero_rows(k_idx, n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
+        rc = launch_zero_rows(reinterpret_cast<const int32_t*>(k_key), n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
     }
-    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_idx, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
+    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
-    rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, d,
+    rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, d,
                                    flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
     if (rc != SCFA_OK) return rc;
-    return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd,
+    return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd,
                                    S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dq, st);
 }
 
@@ -163,23 +164,26 @@ const char* scfa_error_string(int code)
 }
 
 int scfa_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
-                        int32_t* bucket_sorted_out, int32_t* bucket_off_out, void* stream)
+                        int32_t* bucket_sorted_out, int32_t* bucket_off_out, uint32_t* sort_key_out, void* stream)
 {
     if (!bucket || !idx_out || !bucket_off_out || S <= 0 || T <= 0 || nb <= 0) return SCFA_EINVAL;
     if (nb > SCFA_MAX_BUCKETS || S > 0x7fffffff / 1) return SCFA_EUNSUPPORTED;
-    return launch_sort_by_bucket(1, bucket, nullptr, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, nullptr,
-                                 nullptr, nullptr, (hipStream_t)stream);
+    if (sort_key_out && T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;
+    return launch_sort_by_bucket(1, bucket, nullptr, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, sort_key_out,
+                                 nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int scfa_sort_by_bucket_pair(const int32_t* bucket_q, const int32_t* bucket_k, int S, int T, int nb,
-                             int32_t* q_idx_out, int32_t* q_sorted_out, int32_t* q_off_out, int32_t* k_idx_out,
-                             int32_t* k_sorted_out, int32_t* k_off_out, void* stream)
+                             int32_t* q_idx_out, int32_t* q_sorted_out, int32_t* q_off_out, uint32_t* q_sort_key_out,
+                             int32_t* k_idx_out, int32_t* k_sorted_out, int32_t* k_off_out, uint32_t* k_sort_key_out,
+                             void* stream)
 {
     if (!bucket_q || !bucket_k || !q_idx_out || !q_off_out || !k_idx_out || !k_off_out || S <= 0 || T <= 0 || nb <= 0)
         return SCFA_EINVAL;
     if (nb > SCFA_MAX_BUCKETS || S > 0x3fffffff) return SCFA_EUNSUPPORTED;
-    return launch_sort_by_bucket(2, bucket_q, bucket_k, S, T, nb, q_idx_out, q_sorted_out, q_off_out, k_idx_out,
-                                 k_sorted_out, k_off_out, (hipStream_t)stream);
+    if ((q_sort_key_out || k_sort_key_out) && T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;
+    return launch_sort_by_bucket(2, bucket_q, bucket_k, S, T, nb, q_idx_out, q_sorted_out, q_off_out, q_sort_key_out,
+                                 k_idx_out, k_sorted_out, k_off_out, k_sort_key_out, (hipStream_t)stream);
 }
 
 int scfa_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out, void* stream)
@@ -296,12 +300,12 @@ int scfa_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx, c
                                (hipStream_t)stream);
 }
 
-int scfa_hash_attn_fwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,
-                       const int32_t* k_idx, const int32_t* fwd_work, int n_fwd, int B, int H, int T, int d,
+int scfa_hash_attn_fwd(const void* q_perm, const void* k_perm, const void* v_perm, const uint32_t* q_sort_key,
+                       const uint32_t* k_sort_key, const int32_t* fwd_work, int n_fwd, int B, int H, int T, int d,
                        int dtype, float sm_scale, int flags, void* o_out, float* lse_out, void* o_f16_out,
                        void* stream)
 {
-    return attn_fwd_impl(q_perm, k_perm, v_perm, q_idx, k_idx, nullptr, false, fwd_work, n_fwd, B, H, T, d, dtype,
+    return attn_fwd_impl(q_perm, k_perm, v_perm, q_sort_key, k_sort_key, nullptr, false, fwd_work, n_fwd, B, H, T, d, dtype,
                          sm_scale, flags, o_out, lse_out, o_f16_out, (hipStream_t)stream);
 }
 
@@ -310,7 +314,7 @@ int scfa_qkdrop_attn_fwd(const void* q_c, const void* k_c, const void* v_c, cons
                          int H, int T, int d, int dtype, float sm_scale, int flags, void* o_out, float* lse_out,
                          void* o_f16_out, void* stream)
 {
-    return attn_fwd_impl(q_c, k_c, v_c, q_idx, k_idx, n_q, true, fwd_work, n_fwd, B, H, T, d, dtype, sm_scale,
+    return attn_fwd_impl(q_c, k_c, v_c, reinterpret_cast<const uint32_t*>(q_idx), reinterpret_cast<const uint32_t*>(k_idx), n_q, true, fwd_work, n_fwd, B, H, T, d, dtype, sm_scale,
                          flags, o_out, lse_out, o_f16_out, (hipStream_t)stream);
 }
 
@@ -321,13 +325,13 @@ size_t scfa_attn_bwd_workspace_bytes(int S, int T, int d, int dtype)
            align_up((size_t)S * T * 16, 256) + align_up((size_t)S * 64 * 4, 256) + align_up((size_t)S * 4, 256);
 }
 
-int scfa_hash_attn_bwd(const void* q_perm, const void* k_perm, const void* v_perm, const int32_t* q_idx,
-                       const int32_t* k_idx, const int32_t* fwd_work, int n_fwd, const int32_t* bwd_work,
+int scfa_hash_attn_bwd(const void* q_perm, const void* k_perm, const void* v_perm, const uint32_t* q_sort_key,
+                       const uint32_t* k_sort_key, const int32_t* fwd_work, int n_fwd, const int32_t* bwd_work,
                        int n_bwd, const void* o, const void* o_f16, const float* lse, const void* d_o, int B,
                        int H, int T, int d, int dtype, float sm_scale, int flags, float* dq_out, float* dk_out,
                        float* dv_out, void* ws, size_t ws_bytes, void* stream)
 {
-    return attn_bwd_impl(q_perm, k_perm, v_perm, q_idx, k_idx, nullptr, nullptr, false, fwd_work, n_fwd, bwd_work,
+    return attn_bwd_impl(q_perm, k_perm, v_perm, q_sort_key, k_sort_key, nullptr, nullptr, false, fwd_work, n_fwd, bwd_work,
                          n_bwd, o, o_f16, lse, d_o, B, H, T, d, dtype, sm_scale, flags, dq_out, dk_out, dv_out, ws,
                          ws_bytes, (hipStream_t)stream);
 }
@@ -338,7 +342,7 @@ int scfa_qkdrop_attn_bwd(const void* q_c, const void* k_c, const void* v_c, cons
                          const float* lse, const void* d_o, int B, int H, int T, int d, int dtype, float sm_scale, int flags,
                          float* dq_out, float* dk_out, float* dv_out, void* ws, size_t ws_bytes, void* stream)
 {
-    return attn_bwd_impl(q_c, k_c, v_c, q_idx, k_idx, n_q, n_k, true, fwd_work, n_fwd, bwd_work, n_bwd, o, o_f16, lse, d_o,
+    return attn_bwd_impl(q_c, k_c, v_c, reinterpret_cast<const uint32_t*>(q_idx), reinterpret_cast<const uint32_t*>(k_idx), n_q, n_k, true, fwd_work, n_fwd, bwd_work, n_bwd, o, o_f16, lse, d_o,
                          B, H, T, d, dtype, sm_scale, flags, dq_out, dk_out, dv_out, ws, ws_bytes,
                          (hipStream_t)stream);
 }

@@ -110,7 +110,7 @@ __device__ __forceinline__ void split3(float x, uint32_t& w01, uint32_t& w23)
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const uint16_t* __restrict__ o, const uint16_t* __restrict__ o_f16, const float* __restrict__ lse,
-    const uint16_t* __restrict__ d_o, const int32_t* __restrict__ q_idx, const uint32_t* __restrict__ amax_partial,
+    const uint16_t* __restrict__ d_o, const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ amax_partial,
     int n_partial, int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
     uint16_t* __restrict__ aux_perm, float* __restrict__ inv_scale_out)
 {
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     float acc = 0.f;
     int src = 0;
     if (valid) {
-        src = q_idx[seg + r];
+        src = (int)(q_key[seg + r] & KEY_POS_MASK);   // original position of sorted row r
         const uint4 g = *reinterpret_cast<const uint4*>(d_o + (seg + src) * D + c8 * 8);
         const uint32_t gw[4] = {g.x, g.y, g.z, g.w};
         float gs[8], y[8];
@@ -182,7 +182,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     }
 }
 
-int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const int32_t* q_idx,
+int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const uint32_t* q_key,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st)
 {
@@ -195,10 +195,10 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
     if (d == 64)
         hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
-                           q_idx, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_key, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else if (d == 128)
         hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
-                           q_idx, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_key, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ do_perm, const uint16_t* __restrict__ aux_perm,
     const float* __restrict__ inv_scale,
-    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int S, int T, int strict,
     float* __restrict__ dk, float* __restrict__ dv)
 {
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     auto q_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
     auto g_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + Ring::TILE_ELEMS * 2); };
     auto aux_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + Ring::AUX_OFF); };
-    auto qpos_tile = [&](int buf) { return reinterpret_cast<const int32_t*>(smem_raw + buf * BUF_BYTES + Ring::QPOS_OFF); };
+    auto qpos_tile = [&](int buf) { return reinterpret_cast<const uint32_t*>(smem_raw + buf * BUF_BYTES + Ring::QPOS_OFF); };
     const uint32_t lds0 = lds_address(smem_raw);
 
     const int s = blockIdx.x % S;
@@ -258,9 +258,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const int krow = wave * 32 + l32;
     const bool kvalid = krow < k_count;
     const int kr = min(krow, k_count - 1);            // keys past the end repeat the last one; never written
-    const int kpos_ld = k_idx[seg + k_begin + kr];
-    const int kpos = kvalid ? kpos_ld : INT32_MAX;
-    const int kcmp = kvalid ? kpos_ld + strict : INT32_MAX;   // a query is allowed iff its position >= kcmp
+    const uint32_t kkey = k_key[seg + k_begin + kr];
+    const int kpos = (int)(kkey & KEY_POS_MASK);
+    // a query is allowed iff (its sort key - klo) <= kspan: same bucket, position >= the key's (> if strict)
+    const uint32_t klo = kvalid ? kkey + (uint32_t)strict : KEY_NEVER;
+    const uint32_t kspan = kvalid ? KEY_POS_MASK - (uint32_t)(kpos + strict) : 0u;
 
     f16x8 kf[D / 16], vf[D / 16];
     {
@@ -292,17 +294,22 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 
     const int n_tiles = (q_count + BM - 1) / BM;
     const int n_masked = min((q_masked + BM - 1) / BM, n_tiles);   // leading tiles that need the causal test
-    int kmin_wave = kcmp;            // smallest position a query must have to see any key of this wavefront
+    // the sort keys of the queries that may see any key of this wavefront lie in [klo_wave, khi_wave]
+    uint32_t klo_wave = kvalid ? klo : 0xffffffffu, khi_wave = kvalid ? (kkey | KEY_POS_MASK) : 0u;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) kmin_wave = min(kmin_wave, __shfl_xor(kmin_wave, off));
-    kmin_wave = __builtin_amdgcn_readfirstlane(kmin_wave);
+    for (int off = 32; off > 0; off >>= 1) {
+        klo_wave = min(klo_wave, (uint32_t)__shfl_xor((int)klo_wave, off));
+        khi_wave = max(khi_wave, (uint32_t)__shfl_xor((int)khi_wave, off));
+    }
+    klo_wave = __builtin_amdgcn_readfirstlane(klo_wave);
+    khi_wave = __builtin_amdgcn_readfirstlane(khi_wave);
 
     AsyncTile<D, BM, 256> loader;
     loader.init();
     const u32x4 q_desc = make_desc(q + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
     const u32x4 g_desc = make_desc(do_perm + (seg + q_begin) * D, (uint32_t)q_count * D * 2);
     const u32x4 a_desc = make_desc(aux_perm + (seg + q_begin) * 8, (uint32_t)q_count * 16);
-    const u32x4 p_desc = make_desc(q_idx + seg + q_begin, (uint32_t)q_count * 4);
+    const u32x4 p_desc = make_desc(q_key + seg + q_begin, (uint32_t)q_count * 4);
     // Every wavefront issues the same number of loads per tile, so one vmcnt threshold serves all.
     // Rows past the end of the range (and whole tiles past the end) land as zeros everywhere (Q, dO,
     // aux, positions): P = 1 there, but dO = 0 and dP' = 0 make their contributions to dV and dK
@@ -324,7 +331,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         const uint16_t* Qt = q_tile(buf);
         const uint16_t* Gt = g_tile(buf);
         const uint16_t* At = aux_tile(buf);
-        const int32_t* qpos_t = qpos_tile(buf);
+        const uint32_t* qpos_t = qpos_tile(buf);
         f32x16 sacc[2], pacc[2];
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb) {
@@ -344,15 +351,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                int qpa[4] = {0, 0, 0, 0};
+                uint32_t qpa[4] = {0u, 0u, 0u, 0u};
                 if (MASKED) {
-                    const int4 qp = *reinterpret_cast<const int4*>(&qpos_t[qb * 32 + 8 * g + 4 * h]);
+                    const uint4 qp = *reinterpret_cast<const uint4*>(&qpos_t[qb * 32 + 8 * g + 4 * h]);
                     qpa[0] = qp.x; qpa[1] = qp.y; qpa[2] = qp.z; qpa[3] = qp.w;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(sacc[qb][4 * g + e]);
-                    if (MASKED) { if (kcmp > qpa[e]) p = 0.f; }     // causal test on original positions
+                    if (MASKED) { if (qpa[e] - klo > kspan) p = 0.f; }     // bucket and causal test on the sort keys
                     sacc[qb][4 * g + e] = p;
                     pacc[qb][4 * g + e] = p * pacc[qb][4 * g + e];
                 }
@@ -383,12 +390,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;
         issue(jt + NBUF - 1, refill);
-        // positions ascend along the queries of an item: a tile whose last query lies before every
-        // key of this wavefront contributes nothing to it
+        // sort keys ascend along the queries of an item: a tile that lies entirely below or entirely
+        // above what may see the keys of this wavefront contributes nothing to it
         bool skip = false;
         if (MASKED) {
             const int last = min(BM, q_count - jt * BM) - 1;
-            skip = kmin_wave > __builtin_amdgcn_readfirstlane(qpos_tile(cur)[last]);
+            skip = (uint32_t)__builtin_amdgcn_readfirstlane(qpos_tile(cur)[last]) < klo_wave ||
+                   (uint32_t)__builtin_amdgcn_readfirstlane(qpos_tile(cur)[0]) > khi_wave;
         }
         if (!skip) tile(cur, masked_tag);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
@@ -418,7 +426,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 template <int D>
 static int launch_dkdv_t(const void* q, const void* k, const void* v, const void* do_perm,
                          const void* aux_perm, const float* inv_scale,
-                         const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S,
+                         const uint32_t* q_key, const uint32_t* k_key, const int32_t* work, int n_work, int S,
                          int T, int strict, float* dk, float* dv, hipStream_t st)
 {
     const size_t smem = (size_t)DkdvRing<D>::NBUF * DkdvRing<D>::BUF_BYTES;
@@ -430,7 +438,7 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
     }
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
-                       (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_idx, k_idx,
+                       (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_key, k_key,
                        work, n_work, S, T, strict, dk, dv);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
@@ -438,14 +446,14 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
 
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
-                              const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
+                              const uint32_t* q_key, const uint32_t* k_key, const int32_t* bwd_work, int n_bwd,
                               int S, int T, int d, int strict, float* dk, float* dv, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DKDV, st);
     if (d == 64)
-        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, strict, dk, dv, st);
+        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, strict, dk, dv, st);
     if (d == 128)
-        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_idx, k_idx, bwd_work, n_bwd, S, T, strict, dk, dv, st);
+        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, strict, dk, dv, st);
     return SCFA_EUNSUPPORTED;
 }
 
@@ -470,7 +478,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
     const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
-    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict, float* __restrict__ dq)
 {
     constexpr int BN = FWD_TILE_N;
@@ -480,7 +488,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     constexpr int LOADS_PER_TILE = 2 * AsyncTile<D, BN, 256>::ROUNDS + 1;     // per wavefront
     auto k_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
     auto v_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 2); };
-    auto kpos_tile = [&](int buf) { return reinterpret_cast<int32_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 4); };
+    auto kpos_tile = [&](int buf) { return reinterpret_cast<uint32_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 4); };
     const uint32_t lds0 = lds_address(smem_raw);
 
     const int s = blockIdx.x % S;
@@ -495,9 +503,12 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     const int qrow = wave * 32 + l32;
     const bool qvalid = qrow < q_count;
     const int qr = min(qrow, q_count - 1);              // rows past the end repeat the last one; never written
-    const int qpos_ld = q_idx[seg + q_begin + qr];
-    const int qpos = qvalid ? qpos_ld : -1;
-    const int qcmp = qvalid ? qpos_ld - strict : -1;   // a key is allowed iff its position <= qcmp
+    const uint32_t qkey = q_key[seg + q_begin + qr];
+    const int qpos = (int)(qkey & KEY_POS_MASK);
+    // a key is allowed iff (its sort key - qlo) <= qspan: same bucket, position <= the query's (< if strict)
+    const bool some = qvalid && qpos - strict >= 0;
+    const uint32_t qlo = some ? (qkey & ~KEY_POS_MASK) : KEY_NEVER;
+    const uint32_t qspan = some ? (uint32_t)(qpos - strict) : 0u;
     const float lse_ld = lse_perm[seg + q_begin + qr];
     const float lse2 = (qvalid && lse_ld != -INFINITY) ? fmaf(lse_ld, LOG2E, -RTZ_BIAS_LOG2) : INFINITY;
     const float delta = delta_perm[seg + q_begin + qr];
@@ -523,16 +534,21 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
 
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = min(k_nomask / BN, n_tiles);
-    int qmax_wave = qcmp;            // largest position any query of this wavefront may attend to
+    // the sort keys any query of this wavefront may attend to lie in [qlo_wave, qhi_wave]
+    uint32_t qlo_wave = some ? qlo : 0xffffffffu, qhi_wave = some ? qlo + qspan : 0u;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) qmax_wave = max(qmax_wave, __shfl_xor(qmax_wave, off));
-    qmax_wave = __builtin_amdgcn_readfirstlane(qmax_wave);
+    for (int off = 32; off > 0; off >>= 1) {
+        qlo_wave = min(qlo_wave, (uint32_t)__shfl_xor((int)qlo_wave, off));
+        qhi_wave = max(qhi_wave, (uint32_t)__shfl_xor((int)qhi_wave, off));
+    }
+    qlo_wave = __builtin_amdgcn_readfirstlane(qlo_wave);
+    qhi_wave = __builtin_amdgcn_readfirstlane(qhi_wave);
 
     AsyncTile<D, BN, 256> loader;
     loader.init();
     const u32x4 k_desc = make_desc(k + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
     const u32x4 v_desc = make_desc(v + (seg + k_begin) * D, (uint32_t)k_count * D * 2);
-    const u32x4 p_desc = make_desc(k_idx + seg + k_begin, (uint32_t)k_count * 4);
+    const u32x4 p_desc = make_desc(k_key + seg + k_begin, (uint32_t)k_count * 4);
     // every wavefront issues the same number of loads per tile, so one vmcnt threshold serves all;
     // tiles past the end read zeros into a buffer nobody uses
     auto issue = [&](int jt, int buf) {
@@ -548,7 +564,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         constexpr bool MASKED = decltype(masked_tag)::value;
         const uint16_t* Kt = k_tile(buf);
         const uint16_t* Vt = v_tile(buf);
-        const int32_t* kpos_t = kpos_tile(buf);
+        const uint32_t* kpos_t = kpos_tile(buf);
         f32x16 sacc[2], pacc[2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) { sacc[kb] = s_start; pacc[kb] = p_start; }
@@ -564,15 +580,15 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                int kpa[4] = {0, 0, 0, 0};
+                uint32_t kpa[4] = {0u, 0u, 0u, 0u};
                 if (MASKED) {
-                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
+                    const uint4 kp = *reinterpret_cast<const uint4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
                     kpa[0] = kp.x; kpa[1] = kp.y; kpa[2] = kp.z; kpa[3] = kp.w;
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     float p = fast_exp2(sacc[kb][4 * g + e]);
-                    if (MASKED) { if (kpa[e] > qcmp) p = 0.f; }     // causal test on original positions
+                    if (MASKED) { if (kpa[e] - qlo > qspan) p = 0.f; }     // bucket and causal test on the sort keys
                     pacc[kb][4 * g + e] = p * pacc[kb][4 * g + e];
                 }
             }
@@ -599,15 +615,17 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         wait_async<LOADS_PER_TILE * (NBUF - 2)>();
         if (MASKED && lane < KPW) {
             const int key = jt * BN + wave * KPW + lane;
-            if (key >= k_count) kpos_tile(cur)[wave * KPW + lane] = INT32_MAX;   // never allowed
+            if (key >= k_count) kpos_tile(cur)[wave * KPW + lane] = KEY_PAST_END;   // never allowed
         }
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
         issue(jt + NBUF - 1, refill);
-        // positions ascend along the keys of an item: a tile whose first key lies after every query
-        // of this wavefront contributes nothing to it
+        // sort keys ascend along the keys of an item: a tile that lies entirely above or entirely
+        // below what the queries of this wavefront may attend to contributes nothing to it
         bool skip = false;
-        if (MASKED) skip = __builtin_amdgcn_readfirstlane(kpos_tile(cur)[0]) > qmax_wave;
+        if (MASKED)
+            skip = (uint32_t)__builtin_amdgcn_readfirstlane(kpos_tile(cur)[0]) > qhi_wave ||
+                   (uint32_t)__builtin_amdgcn_readfirstlane(kpos_tile(cur)[BN - 1]) < qlo_wave;
         if (!skip) tile(cur, masked_tag);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
@@ -631,7 +649,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
 template <int D>
 static int launch_dq_t(const void* q, const void* k, const void* v, const void* do_perm,
                        const float* lse_perm, const float* delta_perm, const float* inv_scale,
-                       const int32_t* q_idx, const int32_t* k_idx, const int32_t* work, int n_work, int S, int T,
+                       const uint32_t* q_key, const uint32_t* k_key, const int32_t* work, int n_work, int S, int T,
                        float tau, int strict, float* dq, hipStream_t st)
 {
     const size_t smem = (size_t)DqRing<D>::NBUF * DqRing<D>::BUF_BYTES;
@@ -643,7 +661,7 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
     }
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dq_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
-                       (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx,
+                       (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key,
                        work, n_work, S, T, tau, strict, dq);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
@@ -651,14 +669,14 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
 
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
-                            const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,
+                            const uint32_t* q_key, const uint32_t* k_key, const int32_t* fwd_work, int n_fwd,
                             int S, int T, int d, float tau, int strict, float* dq, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DQ, st);
     if (d == 64)
-        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, strict, dq, st);
+        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd, S, T, tau, strict, dq, st);
     if (d == 128)
-        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_idx, k_idx, fwd_work, n_fwd, S, T, tau, strict, dq, st);
+        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd, S, T, tau, strict, dq, st);
     return SCFA_EUNSUPPORTED;
 }
 

@@ -14,13 +14,13 @@ namespace scfa {
 template <int D>
 __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
     const float* __restrict__ q, const float* __restrict__ k, const float* __restrict__ v,
-    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int T, float tau, int strict, float* __restrict__ o,
     float* __restrict__ lse)
 {
     __shared__ float Ks[F32_TILE_N][D];
     __shared__ float Vs[F32_TILE_N][D];
-    __shared__ int32_t kpos[F32_TILE_N];
+    __shared__ uint32_t kkey[F32_TILE_N];   // sort keys: bucket << 24 | position
 
     const int s = blockIdx.y;
     const int32_t* it = work + ((size_t)s * n_work + blockIdx.x) * WORK_STRIDE;
@@ -31,7 +31,12 @@ __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
     const int r = threadIdx.x;
     const bool valid = r < q_count;
     const size_t seg = (size_t)s * T;
-    const int qpos = valid ? q_idx[seg + q_begin + r] : -1;
+    const uint32_t qkey = valid ? q_key[seg + q_begin + r] : 0u;
+    const int qpos = valid ? (int)(qkey & KEY_POS_MASK) : -1;
+    // a key is taken iff (its sort key - qlo) <= qspan: same bucket, position <= the query's (< if strict)
+    const bool some = valid && qpos - strict >= 0;
+    const uint32_t qlo = some ? (qkey & ~KEY_POS_MASK) : KEY_NEVER;
+    const uint32_t qspan = some ? (uint32_t)(qpos - strict) : 0u;
 
     float qr[D], acc[D];
 #pragma unroll
@@ -59,11 +64,11 @@ __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
             reinterpret_cast<float4*>(&Vs[j][0])[c] = vv;
         }
         if (threadIdx.x < F32_TILE_N)
-            kpos[threadIdx.x] = (k0 + threadIdx.x < k_count) ? k_idx[seg + k_begin + k0 + threadIdx.x]
-                                                              : INT32_MAX;
+            kkey[threadIdx.x] = (k0 + threadIdx.x < k_count) ? k_key[seg + k_begin + k0 + threadIdx.x]
+                                                              : KEY_PAST_END;
         __syncthreads();
         for (int j = 0; j < F32_TILE_N; ++j) {
-            if (kpos[j] > qpos - strict) continue;   // causal test on original positions (strict: key must be earlier)
+            if (kkey[j] - qlo > qspan) continue;   // bucket and causal test in one range test
             float sc = 0.f;
 #pragma unroll
             for (int c = 0; c < D; ++c) sc = fmaf(qr[c], Ks[j][c], sc);
@@ -86,16 +91,16 @@ __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
     lse[seg + qpos] = l > 0.f ? m + logf(l) : -INFINITY;
 }
 
-int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const int32_t* q_idx,
-                        const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const uint32_t* q_key,
+                        const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
                         float tau, int strict, float* o, float* lse, hipStream_t st)
 {
     dim3 grid(n_work, S), block(F32_TILE_M);
     ProfScope prof(SCFA_K_FWD, st);
     if (d == 64)
-        hipLaunchKernelGGL(attn_fwd_f32_kernel<64>, grid, block, 0, st, q, k, v, q_idx, k_idx, work, n_work, T, tau, strict, o, lse);
+        hipLaunchKernelGGL(attn_fwd_f32_kernel<64>, grid, block, 0, st, q, k, v, q_key, k_key, work, n_work, T, tau, strict, o, lse);
     else if (d == 128)
-        hipLaunchKernelGGL(attn_fwd_f32_kernel<128>, grid, block, 0, st, q, k, v, q_idx, k_idx, work, n_work, T, tau, strict, o, lse);
+        hipLaunchKernelGGL(attn_fwd_f32_kernel<128>, grid, block, 0, st, q, k, v, q_key, k_key, work, n_work, T, tau, strict, o, lse);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());

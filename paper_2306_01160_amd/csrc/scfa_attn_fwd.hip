@@ -51,7 +51,7 @@ struct FwdRing {
 template <int D, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
+    const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
     uint16_t* __restrict__ o, float* __restrict__ lse, uint16_t* __restrict__ o_f16)
 {
@@ -67,7 +67,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     auto k_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES); };
     auto v_tile = [&](int buf) { return reinterpret_cast<const uint16_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 2); };
-    auto kpos_tile = [&](int buf) { return reinterpret_cast<int32_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 4); };
+    auto kpos_tile = [&](int buf) { return reinterpret_cast<uint32_t*>(smem_raw + buf * BUF_BYTES + TILE_ELEMS * 4); };
     const uint32_t lds0 = lds_address(smem_raw);
 
     // consecutive workgroups take the same work rank of consecutive segments: the longest
@@ -83,7 +83,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
 
-    int qrow[QB], qpos[QB], qcmp[QB];   // qcmp: a key is allowed iff its position <= qcmp
+    int qrow[QB], qpos[QB];
+    // a key is allowed iff (its sort key - qlo) <= qspan: same bucket, position <= the query's (< if strict)
+    uint32_t qlo[QB], qspan[QB];
     bool qvalid[QB];
     f16x8 qf[QB][D / 16];
 #pragma unroll
@@ -91,9 +93,12 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         qrow[b] = (wave * QB + b) * 32 + l32;
         qvalid[b] = qrow[b] < q_count;
         const int qr = min(qrow[b], q_count - 1);          // rows past the end repeat the last one
-        const int qp_ = q_idx[seg + q_begin + qr];
+        const uint32_t qk_ = q_key[seg + q_begin + qr];
+        const int qp_ = (int)(qk_ & KEY_POS_MASK);
         qpos[b] = qvalid[b] ? qp_ : -1;
-        qcmp[b] = qvalid[b] ? qp_ - strict : -1;           // -1: every key is masked
+        const bool some = qvalid[b] && qp_ - strict >= 0;
+        qlo[b] = some ? (qk_ & ~KEY_POS_MASK) : KEY_NEVER;   // KEY_NEVER, span 0: every key is masked
+        qspan[b] = some ? (uint32_t)(qp_ - strict) : 0u;
         const uint16_t* qp = q + (seg + q_begin + qr) * D + h * 8;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) qf[b][kk] = as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16));
@@ -115,16 +120,22 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         m[b] = -INFINITY; thr[b] = -INFINITY; lsum[b] = 0.f;   // the first finite score always raises
     }
 
-    int qmax_wave = qcmp[0];         // largest position any query of this wavefront may attend to
+    // the sort keys any query of this wavefront may attend to lie in [qlo_wave, qhi_wave]
+    uint32_t qlo_wave = 0xffffffffu, qhi_wave = 0u;
 #pragma unroll
-    for (int b = 1; b < QB; ++b) qmax_wave = max(qmax_wave, qcmp[b]);
+    for (int b = 0; b < QB; ++b)
+        if (qlo[b] != KEY_NEVER) { qlo_wave = min(qlo_wave, qlo[b]); qhi_wave = max(qhi_wave, qlo[b] + qspan[b]); }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) qmax_wave = max(qmax_wave, __shfl_xor(qmax_wave, off));
-    qmax_wave = __builtin_amdgcn_readfirstlane(qmax_wave);
+    for (int off = 32; off > 0; off >>= 1) {
+        qlo_wave = min(qlo_wave, (uint32_t)__shfl_xor((int)qlo_wave, off));
+        qhi_wave = max(qhi_wave, (uint32_t)__shfl_xor((int)qhi_wave, off));
+    }
+    qlo_wave = __builtin_amdgcn_readfirstlane(qlo_wave);
+    qhi_wave = __builtin_amdgcn_readfirstlane(qhi_wave);
 
     const uint16_t* kbase = k + (seg + k_begin) * D;
     const uint16_t* vbase = v + (seg + k_begin) * D;
-    const int32_t* kib = k_idx + seg + k_begin;
+    const uint32_t* kib = k_key + seg + k_begin;
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = k_nomask / BN;            // leading tiles that need no mask
 
@@ -155,7 +166,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         constexpr bool MASKED = decltype(masked_tag)::value;
         const uint16_t* Kt = k_tile(buf);
         const uint16_t* Vt = v_tile(buf);
-        const int32_t* kpos_t = kpos_tile(buf);
+        const uint32_t* kpos_t = kpos_tile(buf);
         // S^T = K Q^T - m : [key block kb][query block b]
         f32x16 sacc[2][QB];
 #pragma unroll
@@ -171,18 +182,18 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                 for (int b = 0; b < QB; ++b) sacc[kb][b] = mfma16(a, qf[b][kk], sacc[kb][b]);
             }
 
-        if (MASKED) {   // causal test on original positions
+        if (MASKED) {   // bucket and causal test in one range test on the sort keys
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
-                    const int4 kp = *reinterpret_cast<const int4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
+                    const uint4 kp = *reinterpret_cast<const uint4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
 #pragma unroll
                     for (int b = 0; b < QB; ++b) {
-                        if (kp.x > qcmp[b]) sacc[kb][b][4 * g + 0] = -INFINITY;
-                        if (kp.y > qcmp[b]) sacc[kb][b][4 * g + 1] = -INFINITY;
-                        if (kp.z > qcmp[b]) sacc[kb][b][4 * g + 2] = -INFINITY;
-                        if (kp.w > qcmp[b]) sacc[kb][b][4 * g + 3] = -INFINITY;
+                        if (kp.x - qlo[b] > qspan[b]) sacc[kb][b][4 * g + 0] = -INFINITY;
+                        if (kp.y - qlo[b] > qspan[b]) sacc[kb][b][4 * g + 1] = -INFINITY;
+                        if (kp.z - qlo[b] > qspan[b]) sacc[kb][b][4 * g + 2] = -INFINITY;
+                        if (kp.w - qlo[b] > qspan[b]) sacc[kb][b][4 * g + 3] = -INFINITY;
                     }
                 }
         }
@@ -271,15 +282,17 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         wait_async<LOADS_PER_TILE * (NBUF - 2)>();
         if (MASKED && lane < KPW) {
             const int key = jt * BN + wave * KPW + lane;
-            if (key >= k_count) kpos_tile(cur)[wave * KPW + lane] = INT32_MAX;   // never allowed
+            if (key >= k_count) kpos_tile(cur)[wave * KPW + lane] = KEY_PAST_END;   // never allowed
         }
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;    // the buffer of tile jt - 1
         issue(jt + NBUF - 1, refill);
-        // positions ascend along the keys of an item: a tile whose first key lies after every query
-        // of this wavefront contributes nothing to it
+        // sort keys ascend along the keys of an item: a tile that lies entirely above or entirely
+        // below what the queries of this wavefront may attend to contributes nothing to it
         bool skip = false;
-        if (MASKED) skip = __builtin_amdgcn_readfirstlane(kpos_tile(cur)[0]) > qmax_wave;
+        if (MASKED)
+            skip = (uint32_t)__builtin_amdgcn_readfirstlane(kpos_tile(cur)[0]) > qhi_wave ||
+                   (uint32_t)__builtin_amdgcn_readfirstlane(kpos_tile(cur)[BN - 1]) < qlo_wave;
         if (!skip) tile(cur, masked_tag);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
@@ -319,7 +332,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
 }
 
 template <int D, int NW, int QB>
-static int launch_fwd_t(const void* q, const void* k, const void* v, const int32_t* q_idx, const int32_t* k_idx,
+static int launch_fwd_t(const void* q, const void* k, const void* v, const uint32_t* q_key, const uint32_t* k_key,
                         const int32_t* work, int n_work, int S, int T, float tau, int strict, void* o,
                         float* lse, void* o_f16, hipStream_t st)
 {
@@ -332,19 +345,19 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const int32
     }
     dim3 grid((unsigned)((size_t)S * n_work));
     hipLaunchKernelGGL((attn_fwd_f16_kernel<D, NW, QB>), grid, dim3(NW * 64), smem, st, (const uint16_t*)q,
-                       (const uint16_t*)k, (const uint16_t*)v, q_idx, k_idx, work, n_work, S, T, tau,
+                       (const uint16_t*)k, (const uint16_t*)v, q_key, k_key, work, n_work, S, T, tau,
                        strict, (uint16_t*)o, lse, (uint16_t*)o_f16);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
-int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
-                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const uint32_t* q_key,
+                         const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
                          float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st)
 {
     ProfScope prof(SCFA_K_FWD, st);
-    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
-    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_idx, k_idx, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
+    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_key, k_key, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
+    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_key, k_key, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
     return SCFA_EUNSUPPORTED;
 }
 

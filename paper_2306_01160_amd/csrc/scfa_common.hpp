@@ -36,9 +36,19 @@ struct ProfScope {
 constexpr int WORK_STRIDE = SCFA_WORK_STRIDE;
 
 // forward / dQ items
-constexpr int W_QBEGIN = 0, W_QCOUNT = 1, W_KBEGIN = 2, W_KCOUNT = 3, W_KNOMASK = 4, W_BUCKET = 5;
+constexpr int W_QBEGIN = 0, W_QCOUNT = 1, W_KBEGIN = 2, W_KCOUNT = 3, W_KNOMASK = 4, W_BUCKET = 5, W_NBUCKETS = 6;
 // backward (key-major) items
 constexpr int BW_KBEGIN = 0, BW_KCOUNT = 1, BW_QBEGIN = 2, BW_QCOUNT = 3, BW_QMASKED = 4;
+
+// ---- sort keys ------------------------------------------------------------------
+// The attention kernels identify a sorted row by its sort key, bucket << 24 | original position
+// (scfa_sort_by_bucket's sort_key_out; a compacted index vector of QK-dropping is its own key,
+// the one bucket having id 0).  Keys increase along the sorted rows of a segment, and "same
+// bucket, position <= p" is one unsigned range test: (key - (bucket << 24)) <= p.
+constexpr uint32_t KEY_POS_BITS = 24;
+constexpr uint32_t KEY_POS_MASK = (1u << KEY_POS_BITS) - 1u;
+constexpr uint32_t KEY_PAST_END = 0xffffffffu;   // rows past the end of a ragged tile: match no range
+constexpr uint32_t KEY_NEVER = 0xfffffffeu;      // lower end of the range of a row that may match nothing
 
 // ---- tile configuration -------------------------------------------------------
 constexpr int FWD_TILE_M = 128;  // query rows per workgroup (4 waves x 32)
@@ -50,8 +60,8 @@ constexpr int F32_TILE_N = 32;
 
 // ---- kernel launchers (defined in the .hip files) ---------------------------
 int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
-                          int32_t* idx0, int32_t* sorted0, int32_t* off0, int32_t* idx1, int32_t* sorted1,
-                          int32_t* off1, hipStream_t st);
+                          int32_t* idx0, int32_t* sorted0, int32_t* off0, uint32_t* key0, int32_t* idx1,
+                          int32_t* sorted1, int32_t* off1, uint32_t* key1, hipStream_t st);
 int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
                         int32_t* count0, int32_t* idx1, int32_t* count1, hipStream_t st);
 int launch_lsh_buckets(int n_problems, const void* x0, const void* x1, const float* R, int S, int H, int T, int d,
@@ -64,22 +74,22 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st);
 int launch_zero_rows(const int32_t* idx, const int32_t* count, int S, int T, int row_bytes,
                      void* out0, void* out1, float* vec, float vec_value, hipStream_t st);
-int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const int32_t* q_idx,
-                        const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const uint32_t* q_key,
+                        const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
                         float tau, int strict, float* o, float* lse, hipStream_t st);
-int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const int32_t* q_idx,
-                         const int32_t* k_idx, const int32_t* work, int n_work, int S, int T, int d,
+int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const uint32_t* q_key,
+                         const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
                          float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st);
-int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const int32_t* q_idx,
+int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const uint32_t* q_key,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st);
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
-                              const int32_t* q_idx, const int32_t* k_idx, const int32_t* bwd_work, int n_bwd,
+                              const uint32_t* q_key, const uint32_t* k_key, const int32_t* bwd_work, int n_bwd,
                               int S, int T, int d, int strict, float* dk, float* dv, hipStream_t st);
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
-                            const int32_t* q_idx, const int32_t* k_idx, const int32_t* fwd_work, int n_fwd,
+                            const uint32_t* q_key, const uint32_t* k_key, const int32_t* fwd_work, int n_fwd,
                             int S, int T, int d, float tau, int strict, float* dq, hipStream_t st);
 
 }  // namespace scfa

@@ -36,6 +36,7 @@ struct SortProblem {
     int32_t* idx_out;
     int32_t* key_sorted_out;
     int32_t* off_out;
+    uint32_t* sort_key_out;   // bucket << 24 | position of every sorted row (nullable)
 };
 
 constexpr int SORT_PREFETCH = 16;  // 64-token steps whose keys are loaded together
@@ -53,6 +54,7 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
     int32_t* __restrict__ idx_out = second ? p1.idx_out : p0.idx_out;
     int32_t* __restrict__ key_sorted_out = second ? p1.key_sorted_out : p0.key_sorted_out;
     int32_t* __restrict__ off_out = second ? p1.off_out : p0.off_out;
+    uint32_t* __restrict__ sort_key_out = second ? p1.sort_key_out : p0.sort_key_out;
     const int wave = threadIdx.x >> 6;
     const int lane = threadIdx.x & 63;
     const size_t seg = (size_t)s * T;
@@ -144,6 +146,7 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
             if (valid) {
                 idx_out[seg + pos] = t;
                 if (key_sorted_out) key_sorted_out[seg + pos] = key;
+                if (sort_key_out) sort_key_out[seg + pos] = ((uint32_t)key << KEY_POS_BITS) | (uint32_t)t;
             }
         }
     }
@@ -151,13 +154,13 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
 
 // n_problems: 1 or 2 (bucket1 etc. ignored for 1)
 int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
-                          int32_t* idx0, int32_t* sorted0, int32_t* off0, int32_t* idx1, int32_t* sorted1,
-                          int32_t* off1, hipStream_t st)
+                          int32_t* idx0, int32_t* sorted0, int32_t* off0, uint32_t* key0, int32_t* idx1,
+                          int32_t* sorted1, int32_t* off1, uint32_t* key1, hipStream_t st)
 {
     int nbits = 0;
     while ((1 << nbits) < nb) ++nbits;
     const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
-    const SortProblem p0{bucket0, idx0, sorted0, off0}, p1{bucket1, idx1, sorted1, off1};
+    const SortProblem p0{bucket0, idx0, sorted0, off0, key0}, p1{bucket1, idx1, sorted1, off1, key1};
     ProfScope prof(SCFA_K_SORT, st);
     hipLaunchKernelGGL(stable_sort_small_keys_kernel<false>, dim3(S * n_problems), dim3(SORT_THREADS), smem, st,
                        p0, p1, S, T, nb, nbits);
@@ -170,7 +173,7 @@ int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* kee
 {
     const int nb = 2;
     const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
-    const SortProblem p0{keep0, idx0, nullptr, count0}, p1{keep1, idx1, nullptr, count1};
+    const SortProblem p0{keep0, idx0, nullptr, count0, nullptr}, p1{keep1, idx1, nullptr, count1, nullptr};
     ProfScope prof(SCFA_K_COMPACT, st);
     hipLaunchKernelGGL(stable_sort_small_keys_kernel<true>, dim3(S * n_problems), dim3(SORT_THREADS), smem, st,
                        p0, p1, S, T, nb, 1);

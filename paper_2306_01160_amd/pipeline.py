@@ -39,6 +39,8 @@ class Context:
     k_bucket_sorted: Optional[torch.Tensor] = None
     q_off: Optional[torch.Tensor] = None
     k_off: Optional[torch.Tensor] = None
+    q_sort_key: Optional[torch.Tensor] = None
+    k_sort_key: Optional[torch.Tensor] = None
 
 
 def _seg(x):
@@ -58,22 +60,22 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True, stric
     B, H, T, d = q.shape
     tiles = sc.scfa_tile_config(d, sc.dtype_code(q))
     flags = sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0
-    (q_idx, q_bs, q_off), (k_idx, k_bs, k_off) = sc.scfa_sort_by_bucket_pair(_seg(bucket_q), _seg(bucket_k), nb,
-                                                                             want_sorted=False)
+    (q_idx, q_bs, q_off, q_key), (k_idx, k_bs, k_off, k_key) = sc.scfa_sort_by_bucket_pair(
+        _seg(bucket_q), _seg(bucket_k), nb, want_sorted=False)
     q_p, k_p, v_p = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, to_f16=q.dtype == torch.bfloat16,
                                        q_scale=sc.scfa_q_scale(sm_scale))
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
                                                         want_bwd=need_bwd, flags=flags)
     o_f16 = _o_f16_buffer(q, need_bwd)
-    o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_idx, k_idx, fwd_work, B, H, sm_scale, o_f16_out=o_f16, flags=flags)
+    o, lse = sc.scfa_hash_attn_fwd(q_p, k_p, v_p, q_key, k_key, fwd_work, B, H, sm_scale, o_f16_out=o_f16, flags=flags)
     ctx = Context(sc.SCFA_HASH, B, H, nb, sm_scale, flags, q_p, k_p, v_p, q_idx, k_idx, None, None, fwd_work, bwd_work,
-                  counters, o, lse, o_f16, q_bs, k_bs, q_off, k_off)
+                  counters, o, lse, o_f16, q_bs, k_bs, q_off, k_off, q_key, k_key)
     return o, lse, ctx
 
 
 def hash_backward(ctx: Context, d_o, ws=None, outs=None):
     """dQ, dK, dV (fp32, original order) of hash-sparse attention."""
-    return sc.scfa_hash_attn_bwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_idx, ctx.k_idx, ctx.fwd_work, ctx.bwd_work,
+    return sc.scfa_hash_attn_bwd(ctx.q_p, ctx.k_p, ctx.v_p, ctx.q_sort_key, ctx.k_sort_key, ctx.fwd_work, ctx.bwd_work,
                                  ctx.o, ctx.lse, d_o, ctx.B, ctx.H, ctx.sm_scale, ws=ws, outs=outs, o_f16=ctx.o_f16, flags=ctx.flags)
 
 

@@ -130,11 +130,15 @@ def test_pair_entry_points_match_single_calls(S, T, nb):
     rng = np.random.default_rng(S + T + nb)
     bq = rng.integers(0, nb, (S, T)).astype(np.int32)
     bk = rng.integers(0, nb, (S, T)).astype(np.int32)
-    (qi, qs, qo), (ki, ks, ko) = sc.scfa_sort_by_bucket_pair(_t(bq), _t(bk), nb)
-    for got, b in (((qi, qs, qo), bq), ((ki, ks, ko), bk)):
+    (qi, qs, qo, qkey), (ki, ks, ko, kkey) = sc.scfa_sort_by_bucket_pair(_t(bq), _t(bk), nb)
+    for got, key, b in (((qi, qs, qo), qkey, bq), ((ki, ks, ko), kkey, bk)):
         ref = oracle.sort_by_bucket(b, nb)
         for a, r in zip(got, ref):
             assert np.array_equal(a.cpu().numpy(), r)
+        # sort key of a sorted row = the pair it was ordered by, bucket << 24 | position
+        assert np.array_equal(key.cpu().numpy().astype(np.int64) & 0xffffffff, (ref[1].astype(np.int64) << 24) | ref[0])
+        single = sc.scfa_sort_by_bucket(_t(b), nb, want_sort_key=True)
+        assert torch.equal(single[3], key) and torch.equal(single[0], got[0])
     kq = (rng.random((S, T)) < 0.6).astype(np.uint8)
     kk = (rng.random((S, T)) < 0.3).astype(np.uint8)
     (cqi, cnq), (cki, cnk) = sc.scfa_compact_keep_pair(_t(kq), _t(kk))
