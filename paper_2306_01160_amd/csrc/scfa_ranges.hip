@@ -11,6 +11,10 @@
 //                  (and the prefix with position <= smallest query position needs no mask)
 //   backward item: queries with position >= smallest key position of the tile
 //                  (only those with position < largest key position need a mask)
+// Buckets with fewer rows than a tile would leave most of every tile empty, so consecutive small
+// buckets are put together: as many whole buckets as fit one tile of the tiled side form one
+// item that spans all their rows on both sides.  The kernels tell the buckets of such an item
+// apart by the sort keys (bucket << 24 | position), which they test in every tile of it.
 // Items of a segment are emitted bucket pair by bucket pair, and inside a pair in order of
 // decreasing work.  Workgroups that run at the same time then share the keys / values
 // (forward) or queries / dO rows (backward) of one or two buckets, which stay in the L2 of
@@ -51,7 +55,7 @@ __device__ __forceinline__ int count_lt(const int32_t* __restrict__ a, int n, in
 
 constexpr int ORDER_GROUP = 2;   // buckets whose items are dispatched together
 
-struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket; };
+struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket, n_buckets; };
 
 // ascending sort key: bucket pair first, then decreasing length of the ranged side (< 2^24)
 __device__ __forceinline__ int order_key(int bucket, int b_count)
@@ -69,31 +73,60 @@ template <bool FORWARD, bool STRICT>
 __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_idx,
                            const int32_t* a_off, const int32_t* b_off, int nb, int tile_a,
                            int tile_b, int n_items_max, int32_t* __restrict__ work_out,
-                           long long* counters2, int32_t* s_tile_base, int32_t* s_cost)
+                           long long* counters2, int32_t* s_tile_base, int32_t* s_unit_first, int32_t* s_cost)
 {
-    // tiles per bucket -> exclusive prefix (nb <= 256)
+    // Units (nb <= 256, one thread): a bucket with a tile or more of rows on the tiled side is a
+    // unit of its own; smaller consecutive buckets are taken together while their rows fit one
+    // tile.  A bucket without rows on the tiled side joins only if its other side is shorter than
+    // a tile (it would be computed for nothing).  Tiles per unit -> exclusive prefix.
+    __shared__ int s_n_units;
     if (threadIdx.x == 0) {
-        int acc = 0;
-        for (int b = 0; b < nb; ++b) {
-            s_tile_base[b] = acc;
-            acc += (a_off[b + 1] - a_off[b] + tile_a - 1) / tile_a;
+        int acc = 0, u = 0, b = 0;
+        while (b < nb) {
+            s_unit_first[u] = b;
+            s_tile_base[u] = acc;
+            int rows = a_off[b + 1] - a_off[b];
+            int e = b + 1;
+            const bool alone = rows >= tile_a || (rows == 0 && b_off[b + 1] - b_off[b] >= tile_b);
+            while (!alone && e < nb) {
+                const int r2 = a_off[e + 1] - a_off[e];
+                if (rows + r2 > tile_a || (r2 == 0 && b_off[e + 1] - b_off[e] >= tile_b)) break;
+                rows += r2;
+                ++e;
+            }
+            acc += (rows + tile_a - 1) / tile_a;
+            b = e;
+            ++u;
         }
-        s_tile_base[nb] = acc;
+        s_unit_first[u] = nb;
+        s_tile_base[u] = acc;
+        s_n_units = u;
     }
     __syncthreads();
-    const int n_items = s_tile_base[nb];
+    const int n_units = s_n_units;
+    const int n_items = s_tile_base[n_units];
 
     auto make_item = [&](int w) -> Item {
-        // bucket of item w: last b with tile_base[b] <= w
-        int lo = 0, hi = nb - 1;
+        // unit of item w: last u with tile_base[u] <= w
+        int lo = 0, hi = n_units - 1;
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
             if (s_tile_base[mid] <= w) lo = mid; else hi = mid - 1;
         }
-        const int b = lo;
+        const int b = s_unit_first[lo];
+        const int b_last = s_unit_first[lo + 1] - 1;
         Item it;
         it.bucket = b;
-        it.a_begin = a_off[b] + (w - s_tile_base[b]) * tile_a;
+        it.n_buckets = b_last - b + 1;
+        if (b_last > b) {   // several small buckets: all their rows on both sides, every tile tested
+            it.a_begin = a_off[b];
+            it.a_count = a_off[b_last + 1] - a_off[b];
+            it.b_begin = b_off[b];
+            it.b_count = b_off[b_last + 1] - b_off[b];
+            it.b_extra = FORWARD ? 0 : it.b_count;
+            return it;
+        }
+        it.a_begin = a_off[b] + (w - s_tile_base[lo]) * tile_a;
         it.a_count = min(tile_a, a_off[b + 1] - it.a_begin);
         const int pos_min = a_idx[it.a_begin];
         const int pos_max = a_idx[it.a_begin + it.a_count - 1];
@@ -130,7 +163,7 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_i
             }
             int32_t* o = work_out + (size_t)rank * WORK_STRIDE;
             o[0] = it.a_begin; o[1] = it.a_count; o[2] = it.b_begin; o[3] = it.b_count;
-            o[4] = it.b_extra; o[5] = it.bucket; o[6] = 0; o[7] = 0;
+            o[4] = it.b_extra; o[5] = it.bucket; o[6] = it.n_buckets; o[7] = 0;
             tiles += (it.b_count + tile_b - 1) / tile_b;
             rect += (long long)it.a_count * it.b_count;
         } else {
@@ -165,9 +198,10 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int32_t* s_qoff = smem;                   // [nb+1]
     int32_t* s_koff = s_qoff + nb + 1;        // [nb+1]
     int32_t* s_tile_base = s_koff + nb + 1;   // [nb+1]
+    int32_t* s_unit_first = s_tile_base + nb + 1;   // [nb+1]
     const int n_max_items = n_fwd > n_bwd ? n_fwd : n_bwd;
-    int32_t* s_cost = s_tile_base + nb + 1;   // [max(n_fwd, n_bwd)]
-    int32_t* s_idx = smem + ((3 * (nb + 1) + n_max_items + 3) & ~3);   // [T] when staged, 16-byte aligned
+    int32_t* s_cost = s_unit_first + nb + 1;  // [max(n_fwd, n_bwd)]
+    int32_t* s_idx = smem + ((4 * (nb + 1) + n_max_items + 3) & ~3);   // [T] when staged, 16-byte aligned
     const int s = blockIdx.x;
     const bool backward = blockIdx.y == 1;
     if (variant == SCFA_QKDROP) {
@@ -212,13 +246,13 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int32_t* fw = fwd_work + (size_t)s * n_fwd * WORK_STRIDE;
     int32_t* bw = bwd_work ? bwd_work + (size_t)s * n_bwd * WORK_STRIDE : nullptr;
     if (!backward) {
-        if (strict) build_list<true, true>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd, fw, cnt, s_tile_base, s_cost);
-        else build_list<true, false>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd, fw, cnt, s_tile_base, s_cost);
+        if (strict) build_list<true, true>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd, fw, cnt, s_tile_base, s_unit_first, s_cost);
+        else build_list<true, false>(qi, searched, s_qoff, s_koff, nb, fwd_m, fwd_n, n_fwd, fw, cnt, s_tile_base, s_unit_first, s_cost);
         if (!bwd_work && cnt && threadIdx.x == 0) { cnt[2] = 0; cnt[3] = 0; }
     } else {
         long long* c2 = cnt ? cnt + 2 : nullptr;
-        if (strict) build_list<false, true>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd, bw, c2, s_tile_base, s_cost);
-        else build_list<false, false>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd, bw, c2, s_tile_base, s_cost);
+        if (strict) build_list<false, true>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd, bw, c2, s_tile_base, s_unit_first, s_cost);
+        else build_list<false, false>(ki, searched, s_koff, s_qoff, nb, bwd_n, bwd_m, n_bwd, bw, c2, s_tile_base, s_unit_first, s_cost);
     }
 }
 
@@ -228,7 +262,7 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
                         int32_t* fwd_work, int32_t* bwd_work, int64_t* counters, hipStream_t st)
 {
     const int n_max = n_fwd > n_bwd ? n_fwd : n_bwd;
-    const size_t small = sizeof(int32_t) * ((3 * (size_t)(nb + 1) + (size_t)n_max + 3) & ~(size_t)3);
+    const size_t small = sizeof(int32_t) * ((4 * (size_t)(nb + 1) + (size_t)n_max + 3) & ~(size_t)3);
     const int stage = small + sizeof(int32_t) * (size_t)T <= 144 * 1024 ? 1 : 0;
     const size_t smem = small + (stage ? sizeof(int32_t) * (size_t)T : 0);
     static bool attr_set = false;

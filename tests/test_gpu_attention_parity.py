@@ -33,7 +33,7 @@ def test_config1_hash_fp32_forward():
 
 
 @pytest.mark.parametrize("T,nb,d", [(256, 4, 64), (333, 3, 64), (1000, 2, 128), (130, 1, 64), (64, 8, 128),
-                                    (1, 1, 64), (700, 16, 64)])
+                                    (1, 1, 64), (700, 16, 64), (500, 64, 64)])
 def test_hash_fp32_forward_shapes(T, nb, d):
     _full_check(W.hash_uniform(100 + T, 1, 2, T, d, nb, dtype="f32", passes="fwd"), backward=False)
 
@@ -42,6 +42,29 @@ def test_hash_fp32_forward_shapes(T, nb, d):
                                     (64, 8, 128), (1, 1, 64), (700, 16, 64), (1500, 4, 128)])
 def test_hash_bf16_forward_backward_shapes(T, nb, d):
     _full_check(W.hash_uniform(200 + T, 2, 2, T, d, nb))
+
+
+@pytest.mark.parametrize("T,nb,d,strict", [(1000, 64, 64, False), (1111, 200, 128, False), (2048, 256, 64, False),
+                                           (900, 48, 64, True), (300, 256, 128, True)])
+def test_hash_bf16_buckets_smaller_than_a_tile(T, nb, d, strict):
+    """Many buckets of a few rows each: the schedule puts consecutive buckets into one work item and
+    the kernels tell them apart by the sort keys in every tile."""
+    wl = W.hash_uniform(800 + T, 1, 3, T, d, nb)
+    wl.meta["strict"] = strict
+    _full_check(wl)
+
+
+def test_hash_bf16_small_and_large_buckets_mixed():
+    """Bucket sizes from one row to several tiles in one segment (sizes like 1 / rank), and
+    buckets that have queries but no keys and the reverse."""
+    rng = np.random.default_rng(9)
+    wl = W.hash_uniform(9, 1, 2, 3000, 64, 40)
+    p = 1.0 / np.arange(1, 41); p /= p.sum()
+    wl.lab_q[...] = rng.choice(40, size=wl.lab_q.shape, p=p).astype(np.int32)
+    wl.lab_k[...] = rng.choice(40, size=wl.lab_k.shape, p=p).astype(np.int32)
+    wl.lab_k[wl.lab_k == 17] = 3
+    wl.lab_q[wl.lab_q == 30] = 31
+    _full_check(wl)
 
 
 @pytest.mark.parametrize("T,pq,pk,d", [(512, 0.5, 0.5, 64), (777, 0.3, 0.7, 64), (1025, 1.0, 1.0, 64),

@@ -221,7 +221,9 @@ def _check_order(live):
 def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
     """Several schedules are correct; check what must hold: every allowed pair is covered
     exactly once, claimed mask-free regions are mask-free, ranges are tight, items are
-    ordered by bucket pair and by decreasing work inside a pair, counters match the emitted items."""
+    ordered by bucket pair and by decreasing work inside a pair, counters match the emitted items.
+    An item of several small buckets spans exactly the rows of those buckets on both sides,
+    fits one tile of the tiled side and claims no mask-free region."""
     fm, fn, bn, bm = tiles
     S, T = lab_q.shape
     if variant == sc.SCFA_HASH:
@@ -240,6 +242,8 @@ def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
                                          flags=sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0)
     torch.cuda.synchronize()
     fwd, bwd, cnt = fwd.cpu().numpy(), bwd.cpu().numpy(), cnt.cpu().numpy()
+    qo, ko = q_off.cpu().numpy(), k_off.cpu().numpy()
+    merged = 0
     for s in range(S):
         M = oracle.allowed_mask(lab_q[s], lab_k[s], ovar, strict=strict)[np.ix_(rq[s], rk[s])]   # permuted coordinates
         M[nq[s]:, :] = False; M[:, nk[s]:] = False
@@ -250,16 +254,21 @@ def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
         assert np.all(items[len(live):] == 0), "unused items must trail and be zero"
         _check_order(live)
         tiles_f = 0; rect_f = 0
-        for qb, qc, kb, kc, kn, bucket, _, _ in live:
-            assert 0 < qc <= fm and 0 <= kn <= kc
+        for qb, qc, kb, kc, kn, bucket, nbk, _ in live:
+            assert 0 < qc <= fm and 0 <= kn <= kc and nbk >= 1
             assert not covered[qb:qb + qc].any(); covered[qb:qb + qc] = True
             sub = M[qb:qb + qc]
             assert not sub[:, :kb].any() and not sub[:, kb + kc:].any(), "allowed pair outside the key range"
             assert sub[:, kb:kb + kn].all(), "mask-free prefix contains a masked pair"
-            if kc:
-                assert sub[:, kb + kc - 1].any(), "key range is not tight"
-            if kn < kc:
-                assert not sub[:, kb + kn].all(), "mask-free prefix is not maximal"
+            if nbk > 1:
+                merged += 1
+                assert kn == 0
+                assert (qb, qb + qc) == (qo[s, bucket], qo[s, bucket + nbk]) and (kb, kb + kc) == (ko[s, bucket], ko[s, bucket + nbk])
+            else:
+                if kc:
+                    assert sub[:, kb + kc - 1].any(), "key range is not tight"
+                if kn < kc:
+                    assert not sub[:, kb + kn].all(), "mask-free prefix is not maximal"
             tiles_f += -(-kc // fn); rect_f += qc * kc
         assert np.array_equal(covered[:nq[s]], np.ones(nq[s], bool)) and not covered[nq[s]:].any()
         # backward list
@@ -269,22 +278,29 @@ def _check_schedule(variant, lab_q, lab_k, nb, tiles, strict=False):
         assert np.all(items[len(live):] == 0)
         _check_order(live)
         tiles_b = 0; rect_b = 0
-        for kb, kc, qb, qc, qm, bucket, _, _ in live:
-            assert 0 < kc <= bn and 0 <= qm <= qc
+        for kb, kc, qb, qc, qm, bucket, nbk, _ in live:
+            assert 0 < kc <= bn and 0 <= qm <= qc and nbk >= 1
             assert not covered[kb:kb + kc].any(); covered[kb:kb + kc] = True
             sub = M[:, kb:kb + kc]
             assert not sub[:qb].any() and not sub[qb + qc:].any(), "allowed pair outside the query range"
             assert sub[qb + qm:qb + qc].all(), "unmasked query rows contain a masked pair"
-            if qc:
-                assert sub[qb].any(), "query range is not tight"
-            if qm:
-                assert not sub[qb + qm - 1].all()
+            if nbk > 1:
+                merged += 1
+                assert qm == qc
+                assert (qb, qb + qc) == (qo[s, bucket], qo[s, bucket + nbk]) and (kb, kb + kc) == (ko[s, bucket], ko[s, bucket + nbk])
+            else:
+                if qc:
+                    assert sub[qb].any(), "query range is not tight"
+                if qm:
+                    assert not sub[qb + qm - 1].all()
             tiles_b += -(-qc // bm); rect_b += qc * kc
         assert np.array_equal(covered[:nk[s]], np.ones(nk[s], bool)) and not covered[nk[s]:].any()
         assert cnt[s].tolist() == [tiles_f, rect_f, tiles_b, rect_b]
+    return merged
 
 
-@pytest.mark.parametrize("S,T,nb", [(2, 700, 4), (1, 2048, 16), (3, 300, 1), (1, 129, 3), (2, 64, 8)])
+@pytest.mark.parametrize("S,T,nb", [(2, 700, 4), (1, 2048, 16), (3, 300, 1), (1, 129, 3), (2, 64, 8), (2, 1000, 64),
+                                     (1, 4096, 256), (2, 1500, 24)])
 def test_schedule_hash(S, T, nb):
     rng = np.random.default_rng(T + nb)
     bq = rng.integers(0, nb, (S, T)).astype(np.int32)
@@ -292,7 +308,8 @@ def test_schedule_hash(S, T, nb):
     if nb > 2:
         bk[bk == 2] = 0          # a bucket present in Q but absent in K
         bq[bq == 1] = 0          # and one present in K but absent in Q
-    _check_schedule(sc.SCFA_HASH, bq, bk, nb, sc.scfa_tile_config(64, sc.SCFA_BF16))
+    merged = _check_schedule(sc.SCFA_HASH, bq, bk, nb, sc.scfa_tile_config(64, sc.SCFA_BF16))
+    assert (merged > 0) == (T / nb < 64), "buckets smaller than a tile are put together, larger ones are not"
 
 
 @pytest.mark.parametrize("S,T,pq,pk", [(2, 900, 0.5, 0.5), (1, 2048, 0.3, 0.7), (2, 257, 1.0, 1.0),
