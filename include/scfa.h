@@ -342,6 +342,10 @@ int scfa_prof_enable(int on);      /* returns the previous state */
 int scfa_prof_reset(void);
 /* total_ms / launches (host out-pointers) accumulated since the last reset */
 int scfa_prof_read(int kernel_id, double *total_ms, int *launches);
+/* Workgroups of an attention kernel (SCFA_K_FWD, SCFA_K_BWD_DKDV, SCFA_K_BWD_DQ; bf16 path,
+ * head dimension d) that one compute unit of the current device holds at once, as the HIP
+ * runtime computes it from the kernel's registers and LDS (host out-pointer). */
+int scfa_prof_occupancy(int kernel_id, int d, int *workgroups_per_cu);
 
 #ifdef __cplusplus
 }

@@ -31,7 +31,7 @@ EXPORTS = [
     "scfa_compact_keep", "scfa_q_scale", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
     "scfa_attn_bwd_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
-    "scfa_prof_enable", "scfa_prof_reset", "scfa_prof_read",
+    "scfa_prof_enable", "scfa_prof_reset", "scfa_prof_read", "scfa_prof_occupancy",
 ]
 
 
@@ -76,6 +76,7 @@ def lib():
                                            ci, ci, ci, ci, ci, cf, ci, vp, vp, vp, vp, sz, vp]
         L.scfa_prof_enable.argtypes = [ci]
         L.scfa_prof_read.argtypes = [ci, ctypes.POINTER(ctypes.c_double), ip]
+        L.scfa_prof_occupancy.argtypes = [ci, ci, ip]
         for name in EXPORTS:
             fn = getattr(L, name)
             if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes", "scfa_q_scale"):
@@ -313,6 +314,13 @@ def scfa_prof_enable(on: bool) -> int:
 
 def scfa_prof_reset():
     _check(lib().scfa_prof_reset(), "scfa_prof_reset")
+
+
+def scfa_prof_occupancy(kernel: str, d: int) -> int:
+    """Workgroups of an attention kernel ("fwd", "bwd_dkdv", "bwd_dq") resident per compute unit."""
+    n = ctypes.c_int(0)
+    _check(lib().scfa_prof_occupancy(KERNEL_IDS[kernel], int(d), ctypes.byref(n)), "scfa_prof_occupancy")
+    return n.value
 
 
 def scfa_prof_read(kernel: str):

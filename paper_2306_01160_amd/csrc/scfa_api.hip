@@ -347,6 +347,15 @@ int scfa_qkdrop_attn_bwd(const void* q_c, const void* k_c, const void* v_c, cons
                          (hipStream_t)stream);
 }
 
+int scfa_prof_occupancy(int kernel_id, int d, int* workgroups_per_cu)
+{
+    if (!workgroups_per_cu) return SCFA_EINVAL;
+    if (kernel_id == SCFA_K_FWD) return occupancy_attn_fwd_bf16(d, workgroups_per_cu);
+    if (kernel_id == SCFA_K_BWD_DKDV) return occupancy_attn_bwd_dkdv_bf16(d, workgroups_per_cu);
+    if (kernel_id == SCFA_K_BWD_DQ) return occupancy_attn_bwd_dq_bf16(d, workgroups_per_cu);
+    return SCFA_EUNSUPPORTED;
+}
+
 int scfa_prof_enable(int on)
 {
     std::lock_guard<std::mutex> lk(g_prof_mu);

@@ -444,6 +444,21 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
     return SCFA_OK;
 }
 
+template <int D>
+static int occupancy_dkdv_t(int* out)
+{
+    const size_t smem = (size_t)DkdvRing<D>::NBUF * DkdvRing<D>::BUF_BYTES;
+    SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_f16_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    SCFA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void*>(&attn_bwd_dkdv_f16_kernel<D>), 256, smem));
+    return SCFA_OK;
+}
+
+// workgroups of the dK/dV kernel one CU holds at once
+int occupancy_attn_bwd_dkdv_bf16(int d, int* out)
+{
+    return d == 64 ? occupancy_dkdv_t<64>(out) : d == 128 ? occupancy_dkdv_t<128>(out) : SCFA_EUNSUPPORTED;
+}
+
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
                               const uint32_t* q_key, const uint32_t* k_key, const int32_t* bwd_work, int n_bwd,
@@ -665,6 +680,21 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
                        work, n_work, S, T, tau, strict, dq);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
+}
+
+template <int D>
+static int occupancy_dq_t(int* out)
+{
+    const size_t smem = (size_t)DqRing<D>::NBUF * DqRing<D>::BUF_BYTES;
+    SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_f16_kernel<D>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    SCFA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void*>(&attn_bwd_dq_f16_kernel<D>), 256, smem));
+    return SCFA_OK;
+}
+
+// workgroups of the dQ kernel one CU holds at once
+int occupancy_attn_bwd_dq_bf16(int d, int* out)
+{
+    return d == 64 ? occupancy_dq_t<64>(out) : d == 128 ? occupancy_dq_t<128>(out) : SCFA_EUNSUPPORTED;
 }
 
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,

@@ -351,6 +351,24 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const uint3
     return SCFA_OK;
 }
 
+// workgroups of the forward kernel one CU holds at once (registers, LDS ring)
+int occupancy_attn_fwd_bf16(int d, int* out)
+{
+    if (d == 64) {
+        constexpr size_t smem = (size_t)FwdRing<64>::NBUF * FwdRing<64>::BUF_BYTES;
+        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_f16_kernel<64, 4, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        SCFA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void*>(&attn_fwd_f16_kernel<64, 4, 1>), 256, smem));
+        return SCFA_OK;
+    }
+    if (d == 128) {
+        constexpr size_t smem = (size_t)FwdRing<128>::NBUF * FwdRing<128>::BUF_BYTES;
+        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_f16_kernel<128, 4, 1>), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+        SCFA_HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(out, reinterpret_cast<const void*>(&attn_fwd_f16_kernel<128, 4, 1>), 256, smem));
+        return SCFA_OK;
+    }
+    return SCFA_EUNSUPPORTED;
+}
+
 int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const uint32_t* q_key,
                          const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
                          float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st)

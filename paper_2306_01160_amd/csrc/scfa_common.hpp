@@ -92,4 +92,8 @@ int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const v
                             const uint32_t* q_key, const uint32_t* k_key, const int32_t* fwd_work, int n_fwd,
                             int S, int T, int d, float tau, int strict, float* dq, hipStream_t st);
 
+int occupancy_attn_fwd_bf16(int d, int* out);
+int occupancy_attn_bwd_dkdv_bf16(int d, int* out);
+int occupancy_attn_bwd_dq_bf16(int d, int* out);
+
 }  // namespace scfa

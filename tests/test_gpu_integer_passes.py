@@ -366,3 +366,14 @@ def test_schedule_computes_no_more_than_paper_rule():
         ref = oracle.paper_tile_ranges_hash(q_idx[s].cpu().numpy(), k_idx[s].cpu().numpy(),
                                             q_bs[s].cpu().numpy(), k_bs[s].cpu().numpy(), fm, fn)
         assert int(cnt[s, 0]) <= sum(e - a for a, e in ref)
+
+
+# ------------------------------------------------------------------ measurement aids
+
+def test_occupancy_query():
+    """Workgroups per compute unit as the runtime derives them from registers and LDS: at least one
+    for every attention kernel (a launch would otherwise fail), and no more than the LDS ring allows."""
+    for kernel, ring_bytes in (("fwd", 3 * (64 * 64 * 4 + 256)), ("bwd_dkdv", 3 * 17664), ("bwd_dq", 3 * (64 * 64 * 4 + 256))):
+        n64, n128 = sc.scfa_prof_occupancy(kernel, 64), sc.scfa_prof_occupancy(kernel, 128)
+        print(kernel, n64, n128)
+        assert 1 <= n128 <= n64 <= (160 * 1024) // ring_bytes
