@@ -55,13 +55,14 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def count_allowed_pairs(lab_q, lab_k, nb):
+def count_allowed_pairs(lab_q, lab_k, nb, keep_flags=False):
     """Exact number of allowed pairs: for every query, the keys of its bucket at positions
-    <= its own.  Host-side statistic of the inputs (numpy), used only for reporting."""
+    <= its own (with keep flags: kept keys, for kept queries).  Host-side statistic of the inputs
+    (numpy), used only for reporting."""
     S, T = lab_q.shape
     total = 0
     for s in range(S):
-        for b in range(nb):
+        for b in ([1] if keep_flags else range(nb)):
             qpos = np.flatnonzero(lab_q[s] == b)
             kpos = np.flatnonzero(lab_k[s] == b)
             if qpos.size and kpos.size:
@@ -82,7 +83,7 @@ class HashJob:
             self.q, self.k, self.v, self.do = (torch.from_numpy(a).to(dev).to(torch.bfloat16)
                                                for a in (wl.q, wl.k, wl.v, wl.do))
             self.bq, self.bk = (torch.from_numpy(a).to(dev) for a in (wl.lab_q, wl.lab_k))
-            self.nb, self.tau = wl.nb, wl.tau
+            self.nb, self.tau = (None if wl.variant == "qkdrop" else wl.nb), wl.tau
         else:
             self.q, self.k, self.v, self.do, self.bq, self.bk = tensors
             self.nb, self.tau = nb, tau
@@ -133,15 +134,17 @@ def cpu_baseline(wl, n_seg):
     import oracle
     S, T, d = wl.S, wl.T, wl.d
     seg = lambda a: a.reshape(S, T, -1)[:n_seg].astype(np.float64)
+    drop = wl.variant == "qkdrop"
     lq = wl.lab_q.reshape(S, T)[:n_seg].astype(np.int32)
     lk = wl.lab_k.reshape(S, T)[:n_seg].astype(np.int32)
     Q, K, V, dO = seg(wl.q), seg(wl.k), seg(wl.v), seg(wl.do)
+    variant = oracle.QKDROP if drop else oracle.HASH
     t0 = time.perf_counter()
-    oracle.attention_forward(Q, K, V, lq, lk, oracle.HASH, wl.tau)
+    oracle.attention_forward(Q, K, V, lq, lk, variant, wl.tau)
     t1 = time.perf_counter()
-    oracle.attention_backward(Q, K, V, dO, lq, lk, oracle.HASH, wl.tau)
+    oracle.attention_backward(Q, K, V, dO, lq, lk, variant, wl.tau)
     t2 = time.perf_counter()
-    pairs = count_allowed_pairs(lq, lk, wl.nb)
+    pairs = count_allowed_pairs(lq, lk, wl.nb, keep_flags=drop)
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     return {"value": pairs * 14 * d / (t2 - t0) / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
             "sample": f"{n_seg} of {S} (batch, head) segments of the same workload, all rows, fwd+bwd, fp64",
@@ -223,10 +226,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="c4", choices=["c4", "c3"])
+    ap.add_argument("--workload", default="c4", choices=["c4", "c3", "c5"],
+                    help="c4 (default) is the configuration the metric is quoted on; c3 and c5 are the other two "
+                         "large configurations (hash T=8192 nb=16; QK-dropping T=32768 d=128)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense-twin", action="store_true")
-    ap.add_argument("--cpu-segments", type=int, default=24)
+    ap.add_argument("--cpu-segments", type=int, default=None,
+                    help="segments the CPU oracle is timed on (default: 24, or 4 for c5: about 10-30 s of CPU work)")
     ap.add_argument("--sweep", default=None, choices=["hash", "qkdrop"])
     args = ap.parse_args()
     if args.gpus != 1:
@@ -246,10 +252,15 @@ def main():
         sys.exit("bench.py: no GPU visible")
     sc.lib()   # fail loudly if the HIP library is missing
 
-    make = (lambda nb: W.config4(nb=nb)) if args.workload == "c4" else \
-           (lambda nb: W.hash_lsh(3, 4, 12, 8192, 64, nb, name=f"c3_hash_T8192_nb{nb}"))
-    nb = 8 if args.workload == "c4" else 16
-    log(f"[bench] generating workload {args.workload} (nb={nb}) ...")
+    drop = args.workload == "c5"
+    if args.workload == "c4":
+        make = lambda nb: W.config4(nb=nb)
+    elif args.workload == "c3":
+        make = lambda nb: W.hash_lsh(3, 4, 12, 8192, 64, nb, name=f"c3_hash_T8192_nb{nb}")
+    else:   # nb == 1 stands for "nothing dropped" (the dense causal twin)
+        make = lambda nb: W.config5(keep_q=1.0, keep_k=1.0) if nb == 1 else W.config5()
+    nb = {"c4": 8, "c3": 16, "c5": 0}[args.workload]
+    log(f"[bench] generating workload {args.workload} ...")
     wl = make(nb)
     S, T, d = wl.S, wl.T, wl.d
     job = HashJob(wl)
@@ -260,7 +271,7 @@ def main():
     counters = job.ctx.counters.cpu().numpy().sum(0)
     fm, fn, bn, bm = sc.scfa_tile_config(d, sc.SCFA_BF16)
     fwd_tiles, bwd_tiles = int(counters[0]), int(counters[2])
-    pairs = count_allowed_pairs(wl.lab_q.reshape(S, T), wl.lab_k.reshape(S, T), wl.nb)
+    pairs = count_allowed_pairs(wl.lab_q.reshape(S, T), wl.lab_k.reshape(S, T), wl.nb, keep_flags=drop)
 
     # algorithmic flops per launch of each attention kernel (recomputation not counted)
     flops = {"fwd": fwd_tiles * fm * fn * 4 * d,          # S and P.V
@@ -277,8 +288,10 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"hash-sparse LSH nb={wl.nb}, B={wl.B}, H={wl.H}, T={T}, d={d}, fwd+bwd "
-                               f"(benchmark configuration {'4' if args.workload == 'c4' else '3'})",
+        "config": {"workload": (f"QK-dropping keep 0.5 (queries) / 0.3 (keys), B={wl.B}, H={wl.H}, T={T}, d={d}, fwd+bwd "
+                                f"(benchmark configuration 5)" if drop else
+                                f"hash-sparse LSH nb={wl.nb}, B={wl.B}, H={wl.H}, T={T}, d={d}, fwd+bwd "
+                                f"(benchmark configuration {'4' if args.workload == 'c4' else '3'})"),
                    "tiles": {"fwd": [fm, fn], "bwd": [bm, bn]}},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
@@ -294,7 +307,7 @@ def main():
     }
 
     # the bucketing step in front of the path (not part of `value`: the benchmark gives buckets for free)
-    if nb > 1:
+    if nb > 1:   # hash variant only
         R = torch.randn((wl.H, d, nb // 2), device="cuda:0", dtype=torch.float32)
         xq, xk = job.q.reshape(S, T, d), job.k.reshape(S, T, d)
         for _ in range(2):
@@ -330,8 +343,9 @@ def main():
         torch.cuda.empty_cache()
 
     if not args.no_cpu_baseline:
-        log(f"[bench] CPU oracle on {args.cpu_segments} segments ...")
-        result["cpu_baseline"] = cpu_baseline(wl, min(args.cpu_segments, S))
+        n_seg = min(args.cpu_segments or (4 if drop else 24), S)
+        log(f"[bench] CPU oracle on {n_seg} segments ...")
+        result["cpu_baseline"] = cpu_baseline(wl, n_seg)
 
     print(json.dumps(result), flush=True)
 

@@ -132,7 +132,7 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const uint
         rc = launch_zero_rows(reinterpret_cast<const int32_t*>(k_key), n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
     }
-    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
+    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, qkdrop ? n_q : nullptr, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
     rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, d,
                                    flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);

@@ -110,7 +110,8 @@ __device__ __forceinline__ void split3(float x, uint32_t& w01, uint32_t& w23)
 template <int D>
 __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const uint16_t* __restrict__ o, const uint16_t* __restrict__ o_f16, const float* __restrict__ lse,
-    const uint16_t* __restrict__ d_o, const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ amax_partial,
+    const uint16_t* __restrict__ d_o, const uint32_t* __restrict__ q_key, const int32_t* __restrict__ n_q,
+    const uint32_t* __restrict__ amax_partial,
     int n_partial, int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
     uint16_t* __restrict__ aux_perm, float* __restrict__ inv_scale_out)
 {
@@ -119,7 +120,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const size_t seg = (size_t)s * T;
     const int r = (blockIdx.x * 256 + threadIdx.x) / LPR;
     const int c8 = threadIdx.x % LPR;
-    const bool valid = r < T;
+    const bool valid = r < (n_q ? n_q[s] : T);   // rows of dropped queries are never read by the kernels
     __shared__ uint32_t s_amax;
     if (threadIdx.x < 64) {   // reduce the segment's partial maxima
         uint32_t m = (int)threadIdx.x < n_partial ? amax_partial[(size_t)s * AMAX_BLOCKS + threadIdx.x] : 0u;
@@ -183,6 +184,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
 }
 
 int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const uint32_t* q_key,
+                         const int32_t* n_q,
                          int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st)
 {
@@ -195,10 +197,10 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
     if (d == 64)
         hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
-                           q_key, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_key, n_q, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else if (d == 128)
         hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
-                           q_key, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_key, n_q, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());
