@@ -582,43 +582,61 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         const uint16_t* Kt = k_tile(buf);
         const uint16_t* Vt = v_tile(buf);
         const uint32_t* kpos_t = kpos_tile(buf);
-        f32x16 sacc[2], pacc[2];
+        // KBS 32-key blocks of the tile are in flight at once: both at d = 64; one at a time at
+        // d = 128, where two sets of score accumulators would push the kernel past 256 registers
+        // and down to one wavefront per SIMD
+        constexpr int KBS = D == 64 ? 2 : 1;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) { sacc[kb] = s_start; pacc[kb] = p_start; }
+        for (int k0 = 0; k0 < 2; k0 += KBS) {
+            f32x16 sacc[KBS], pacc[KBS];
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
+            for (int kb = 0; kb < KBS; ++kb) {
+                if (KBS == 2) {
+                    sacc[kb] = s_start; pacc[kb] = p_start;     // read as the C operand of the first MFMA: no moves
+                } else {                                        // registers are scarcer than moves at d = 128
+                    float s0 = s_start[0], p0 = p_start[0];
+                    asm volatile("" : "+v"(s0), "+v"(p0));      // not a loop invariant: splat here, every time
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                sacc[kb] = mfma16(swz_rows<D>(Kt, kb * 32 + l32, kk * 16 + h * 8), qf[kk], sacc[kb]);
-                pacc[kb] = mfma16(swz_rows<D>(Vt, kb * 32 + l32, kk * 16 + h * 8), gf[kk], pacc[kb]);
-            }
-
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                uint32_t kpa[4] = {0u, 0u, 0u, 0u};
-                if (MASKED) {
-                    const uint4 kp = *reinterpret_cast<const uint4*>(&kpos_t[kb * 32 + 8 * g + 4 * h]);
-                    kpa[0] = kp.x; kpa[1] = kp.y; kpa[2] = kp.z; kpa[3] = kp.w;
-                }
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(sacc[kb][4 * g + e]);
-                    if (MASKED) { if (kpa[e] - qlo > qspan) p = 0.f; }     // bucket and causal test on the sort keys
-                    pacc[kb][4 * g + e] = p * pacc[kb][4 * g + e];
+                    for (int i = 0; i < 16; ++i) { sacc[kb][i] = s0; pacc[kb][i] = p0; }
                 }
             }
+#pragma unroll
+            for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+                for (int kb = 0; kb < KBS; ++kb) {
+                    sacc[kb] = mfma16(swz_rows<D>(Kt, (k0 + kb) * 32 + l32, kk * 16 + h * 8), qf[kk], sacc[kb]);
+                    pacc[kb] = mfma16(swz_rows<D>(Vt, (k0 + kb) * 32 + l32, kk * 16 + h * 8), gf[kk], pacc[kb]);
+                }
 
 #pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4) {
-            const f16x8 sf = pack_chunk(pacc[c4 >> 1], c4 & 1);
+            for (int kb = 0; kb < KBS; ++kb)
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db) {
-                int oa, ob;
-                swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
-                dqacc[db] = mfma16(swz_trans(Kt, oa, ob), sf, dqacc[db]);
+                for (int g = 0; g < 4; ++g) {
+                    uint32_t kpa[4] = {0u, 0u, 0u, 0u};
+                    if (MASKED) {
+                        const uint4 kp = *reinterpret_cast<const uint4*>(&kpos_t[(k0 + kb) * 32 + 8 * g + 4 * h]);
+                        kpa[0] = kp.x; kpa[1] = kp.y; kpa[2] = kp.z; kpa[3] = kp.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float p = fast_exp2(sacc[kb][4 * g + e]);
+                        if (MASKED) { if (kpa[e] - qlo > qspan) p = 0.f; }     // bucket and causal test on the sort keys
+                        pacc[kb][4 * g + e] = p * pacc[kb][4 * g + e];
+                    }
+                }
+
+#pragma unroll
+            for (int c = 0; c < 2 * KBS; ++c) {
+                const int c4 = 2 * k0 + c;       // 16-key chunk of the tile
+                const f16x8 sf = pack_chunk(pacc[c >> 1], c & 1);
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) {
+                    int oa, ob;
+                    swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
+                    dqacc[db] = mfma16(swz_trans(Kt, oa, ob), sf, dqacc[db]);
+                }
             }
+            if (KBS == 1) __builtin_amdgcn_sched_barrier(0);   // keep the two blocks apart
         }
     };
 
