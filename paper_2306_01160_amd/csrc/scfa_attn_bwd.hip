@@ -9,6 +9,9 @@
 // Three kernels: a pre-pass (D, and dO / LSE brought into permuted order), a key-major
 // kernel for dK and dV (backward work list), and a query-major kernel for dQ (forward
 // work list).  Nothing is accumulated with atomics, so results are deterministic.
+// As in the forward, tiles that need a mask test bucket and causality at once on the rows'
+// sort keys (bucket << 24 | original position), and a wavefront skips a masked tile that
+// lies entirely outside the range its own 32 rows can match.
 //
 // dO is multiplied by a power of two per (batch, head) segment so that its largest
 // magnitude lies in [1, 2) before it is converted to fp16; the gradients are multiplied

@@ -1,10 +1,13 @@
 // Forward attention over the work list, fp16 compute format, fp32 accumulation.
 //
-// A workgroup owns one work item: 128 query rows of one bucket and the range of keys
-// of the same bucket that causality can let through (scfa_block_ranges).  Keys are
-// walked 64 at a time; tiles the schedule proved mask-free come first and run without
-// any test, the remaining (diagonal) tiles apply the causal test on original positions
-// (paper Sec. 3.1 / 3.2: a local causal mask from the index vectors).
+// A workgroup owns one work item: up to 128 query rows of one bucket and the range of keys
+// of the same bucket that causality can let through, or all rows of a few small buckets on
+// both sides (scfa_block_ranges).  Keys are walked 64 at a time; tiles the schedule proved
+// mask-free come first and run without any test, the remaining tiles test bucket and
+// causality at once on the rows' sort keys, bucket << 24 | original position (paper
+// Sec. 3.1 / 3.2: a local mask from the index and bucket vectors).  Sort keys ascend along
+// an item's keys, so a wavefront also skips a masked tile that lies entirely outside the
+// key range its own 32 queries can match.
 //
 // A wavefront keeps its query rows in the lanes: S^T = K Q^T puts one query per lane
 // (column) and 16 keys per accumulator block in its registers, so the softmax
