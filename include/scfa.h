@@ -295,7 +295,9 @@ int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
  * q_perm carries tau * log2(e) as in the forward.  dtype: SCFA_BF16 only.  Per query the
  * kernels hold LSE * log2(e) and D * (power-of-two dO scale) as sums of three fp16
  * numbers; magnitudes above 60000 are clamped there (|D| <= 2 d max|O| after the
- * scaling of dO, so this needs |O| in the thousands).
+ * scaling of dO, so this needs |O| in the thousands).  dS = P (dP - D) is formed in fp16:
+ * |<dO_i, V_j> - D_i| (dO scaled to a largest magnitude in [1, 2)) must stay below the
+ * fp16 range, 65504, i.e. |V| in the hundreds at the least.
  *
  * scfa_qkdrop_attn_bwd additionally takes n_q, n_k [S] (kept counts).
  */

@@ -27,7 +27,10 @@
 //     of that step is the constant (-1, -2^-11, -2^-11, 0 | 0, 0, 0, 0) for the score
 //     and (0, 0, 0, 0 | -1, -2^-11, -2^-11, 0) for dP.  Products of fp16 numbers are exact
 //     in the fp32 accumulation, so the split only costs the final fp32 rounding.
-// What is left per element is one exponential, one product and the fp16 packing.
+// What is left per element is one exponential, one product and the fp16 packing.  The dK/dV
+// kernel needs both P and dS in fp16, so it packs P and dP - D and multiplies the packed
+// pairs (v_pk_mul_f16: half an instruction per element, one more fp16 rounding in dS); P <= 1
+// keeps that product finite for any finite |dP - D| below the fp16 range.
 #include "scfa_common.hpp"
 #include "scfa_mma.hpp"
 
@@ -366,14 +369,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
                     float p = fast_exp2(sacc[qb][4 * g + e]);
                     if (MASKED) { if (qpa[e] - klo > kspan) p = 0.f; }     // bucket and causal test on the sort keys
                     sacc[qb][4 * g + e] = p;
-                    pacc[qb][4 * g + e] = p * pacc[qb][4 * g + e];
                 }
             }
 
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) {
             const f16x8 pf = pack_chunk(sacc[c4 >> 1], c4 & 1);
-            const f16x8 sf = pack_chunk(pacc[c4 >> 1], c4 & 1);
+            const f16x8 sf = pf * pack_chunk(pacc[c4 >> 1], c4 & 1);   // dS = P (dP - D), two elements per instruction
 #pragma unroll
             for (int db = 0; db < D / 32; ++db) {
                 int oa, ob;
