@@ -27,7 +27,11 @@
 // rows): the accumulator is un-normalised and divided by the sum once at the end.  The
 // reference maximum m is only raised when some row's tile maximum exceeds it by more
 // than LAZY_LOG2 (then the accumulator and the sum are rescaled by 2^(m_old - m_new));
-// between raises P = 2^(x - m) may exceed 1 but stays far inside the fp16 range.  Because
+// between raises P = 2^(x - m) may exceed 1 but stays inside the fp16 range.  Once every
+// row of a wavefront has a finite reference, the tile maximum is not even computed: the
+// row sum of the packed probabilities, needed anyway, exceeds 2^15 in some lane whenever
+// a probability has left the fp16 range (packing truncates to at most 65504), and only
+// then is the tile redone with its maximum as the new reference.  Because
 // m changes rarely, -m is kept splatted over an accumulator block and the score
 // contraction starts from it: the matrix core delivers x - m and the only per-element
 // vector work left is the exponential, the packing and the row sum.  A row that never
@@ -43,6 +47,7 @@
 namespace scfa {
 
 constexpr float LAZY_LOG2 = 6.0f;
+constexpr float SUM_LIMIT = 32768.f;   // a lane's tile sum above this may hide a probability beyond the fp16 range
 
 // LDS ring of the forward kernel: as many buffers as three resident workgroups allow
 template <int D>
@@ -165,6 +170,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) swz_trans_offsets<D>(c4 * 16, db * 32, lane, v_off[c4][db][0], v_off[c4][db][1]);
 
+    bool settled = false;   // every row of this wavefront has a finite reference maximum (wave-uniform)
     auto tile = [&](int buf, auto masked_tag) {
         constexpr bool MASKED = decltype(masked_tag)::value;
         const uint16_t* Kt = k_tile(buf);
@@ -202,6 +208,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         }
 
         // lane-local tile maximum per query; raise the reference only when needed
+        auto raise_ref = [&]() {
         float mx[QB];
         bool raise = false;
 #pragma unroll
@@ -240,9 +247,13 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                 thr[b] = m_new == -INFINITY ? -INFINITY : LAZY_LOG2;
             }
         }
+        };
 
-        // P = 2^(x - m), packed to fp16; row sums from the packed values
+        // P = 2^(x - m), packed to fp16 (truncating: at most 65504, never inf); row sums from the
+        // packed values
         f16x8 pf[QB][4];
+        float lt[QB];
+        auto exp_pack = [&]() {
 #pragma unroll
         for (int b = 0; b < QB; ++b) {
             float l0 = 0.f, l1 = 0.f;
@@ -261,8 +272,32 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                     l0 = add_pair(wv[2], l0); l1 = add_pair(wv[3], l1);
                     pf[b][kb * 2 + cc] = as_f16x8(make_uint4(wv[0], wv[1], wv[2], wv[3]));
                 }
-            lsum[b] += l0 + l1;
+            lt[b] = l0 + l1;
         }
+        };
+
+        // Until every row of the wavefront has a finite reference the tile maximum is taken first.
+        // After that the maximum is not computed at all: the sum of the packed probabilities,
+        // which is needed anyway, tells whether any of them left the fp16 range (a probability
+        // beyond 2^15 makes its lane's sum exceed 2^15), and only then is the tile redone with
+        // its maximum as the new reference.
+        const bool by_sum = settled;
+        if (!by_sum) {
+            raise_ref();
+            bool unset = false;
+#pragma unroll
+            for (int b = 0; b < QB; ++b) unset |= thr[b] == -INFINITY;
+            settled = __ballot(unset) == 0ull;
+        }
+        exp_pack();
+        if (by_sum) {
+            bool big = false;
+#pragma unroll
+            for (int b = 0; b < QB; ++b) big |= lt[b] > SUM_LIMIT;
+            if (__ballot(big) != 0ull) { raise_ref(); exp_pack(); }
+        }
+#pragma unroll
+        for (int b = 0; b < QB; ++b) lsum[b] += lt[b];
 
         // O^T += V^T P^T
 #pragma unroll

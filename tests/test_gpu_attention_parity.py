@@ -77,6 +77,30 @@ def test_qkdrop_fp32_forward():
     _full_check(W.qkdrop_bernoulli(7, 1, 2, 300, 64, 0.5, 0.5, dtype="f32", passes="fwd"), backward=False)
 
 
+def test_scores_growing_along_the_sequence():
+    """Scores that rise by ~40 base-2 units from the first key to the last: the forward's reference
+    maximum, taken from a row's first tiles, falls far behind and has to be raised several times
+    (probabilities computed against a stale reference leave the fp16 range; the kernel has to
+    notice, and redo the tile).  The scaled queries are rounded to 11 significant bits, so a score
+    s, and with it the logsumexp, carries a relative error of up to 2^-12: the LSE bound here is
+    1e-3 + 2.5e-4 max|LSE| instead of the plain 1e-3 that holds for O(1) scores."""
+    T, d = 1500, 64
+    wl = W.hash_uniform(31, 1, 2, T, d, 1)
+    rng = np.random.default_rng(31)
+    u = np.where(rng.random(d) < 0.5, -1.0, 1.0).astype(np.float32)
+    ramp = (np.arange(T, dtype=np.float32) / T)[:, None]
+    wl.q[...] = u                                          # tau <q, k_j> = 8 * 3.75 * j / T
+    wl.k[...] = W.round_to_bf16((np.float32(3.75) * ramp * u).astype(np.float32))
+    o, lse, grads, _ = run_gpu(wl)
+    errs = compare_forward(wl, o, lse)
+    errs.update(compare_backward(wl, grads))
+    print(wl.name, {k: f"{v:.2e}" for k, v in errs.items()})
+    lse_max = float(np.abs(lse.cpu().numpy()).max())
+    assert lse_max > 25.0
+    assert errs["LSE"] <= 1e-3 + 2.5e-4 * lse_max
+    assert max(errs["O"], errs["dQ"], errs["dK"], errs["dV"]) <= 2e-2
+
+
 # --------------------------------------------------------------- strictly-causal mask
 
 def _strict(wl, shared_qk=False):
