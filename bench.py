@@ -36,10 +36,13 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA peak (published)
 
 
-def measured_traffic(kernel):
-    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary (FETCH_SIZE and
-    WRITE_SIZE runs, scaled by a copy of known size); None if no summary covers it."""
-    path = os.path.join(ROOT, "profiles", "scfa_hot_path_config4_hash_T16384.md")
+def measured_traffic(kernel, workload="c4"):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of `workload`
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy of known size); None if no summary covers it."""
+    name = {"c4": "scfa_hot_path_config4_hash_T16384.md", "c5": "scfa_hot_path_config5_qkdrop_T32768_d128.md"}.get(workload)
+    if name is None:
+        return None
+    path = os.path.join(ROOT, "profiles", name)
     names = {"bwd_dkdv": "attn_bwd_dkdv_f16_kernel", "bwd_dq": "attn_bwd_dq_f16_kernel", "fwd": "attn_fwd_f16_kernel"}
     try:
         for line in open(path):
@@ -295,7 +298,7 @@ def main():
                    "tiles": {"fwd": [fm, fn], "bwd": [bm, bn]}},
         "roofline": {"bound": "mfma", "kernel": dominant, "achieved": ach, "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": ach / PEAK_BF16_TFLOPS,
-                     "traffic": measured_traffic(dominant) if args.workload == "c4" else None,
+                     "traffic": measured_traffic(dominant, args.workload),
                      "avg_launch_ms": kt[dominant]["avg_ms"]},
         "computed_tile_tflops_kernels": computed_tile_flops / (attn_ms * 1e-3) / 1e12,
         "computed_tile_frac_of_mfma_peak": computed_tile_flops / (attn_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
