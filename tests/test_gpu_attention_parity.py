@@ -224,6 +224,28 @@ def test_two_runs_are_bit_identical():
         assert torch.equal(a, b)
 
 
+def test_side_stream_gives_the_same_bits():
+    """All work is enqueued on the caller's stream: a whole forward + backward issued on a second
+    stream (default priority), with the per-kernel event timers switched on, returns bit for bit
+    what the default stream returns."""
+    from paper_2306_01160_amd import binding as sc
+    for wl in (W.hash_uniform(46, 1, 2, 1300, 64, 6), W.qkdrop_bernoulli(47, 1, 2, 900, 128, 0.6, 0.4)):
+        o1, l1, g1, _ = run_gpu(wl)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        sc.scfa_prof_reset(); sc.scfa_prof_enable(True)
+        with torch.cuda.stream(side):
+            o2, l2, g2, _ = run_gpu(wl)
+        sc.scfa_prof_enable(False)
+        ms, n = sc.scfa_prof_read("fwd")
+        sc.scfa_prof_reset()
+        torch.cuda.synchronize()
+        assert n == 1 and ms > 0.0
+        assert torch.equal(o1, o2) and torch.equal(l1, l2)
+        for a, b in zip(g1, g2):
+            assert torch.equal(a, b)
+
+
 # --------------------------------------------------------------- benchmark configurations
 
 def test_config2_qkdrop_bf16():
