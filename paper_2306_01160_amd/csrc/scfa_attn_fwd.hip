@@ -281,7 +281,9 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         // which is needed anyway, tells whether any of them left the fp16 range (a probability
         // beyond 2^15 makes its lane's sum exceed 2^15), and only then is the tile redone with
         // its maximum as the new reference.
-        const bool by_sum = settled;
+        // (d = 64 only: at d = 128 the matrix cores, not the vector units, set the pace, and keeping
+        // the scores alive for a possible second pass costs more than the maxima it saves)
+        const bool by_sum = D == 64 && settled;
         if (!by_sum) {
             raise_ref();
             bool unset = false;
