@@ -90,11 +90,20 @@ const char *scfa_error_string(int code);
  *                      are ordered by, packed as bucket << 24 | position; increasing
  *                      along r.  The hash-sparse attention entry points take these: "same
  *                      bucket and position <= p" is one range test on them.
+ *   ws, ws_bytes       (nullable) device scratch of scfa_sort_workspace_bytes(S, T, nb)
+ *                      bytes, 4-byte aligned, contents undefined afterwards.  With it, long
+ *                      sequences (T >= 8192) in few segments are cut into chunks that
+ *                      several workgroups sort (a counting kernel runs first); without it,
+ *                      or when it is too small, one workgroup sorts a segment.  The
+ *                      outputs are the same bits either way.
  * Limits: 1 <= nb <= SCFA_MAX_BUCKETS, 1 <= T, 1 <= S.
  */
+size_t scfa_sort_workspace_bytes(int S, int T, int nb);   /* also for the compaction (any nb) */
+
 int scfa_sort_by_bucket(const int32_t *bucket, int S, int T, int nb,
                         int32_t *idx_out, int32_t *bucket_sorted_out,
-                        int32_t *bucket_off_out, uint32_t *sort_key_out, void *stream);
+                        int32_t *bucket_off_out, uint32_t *sort_key_out,
+                        void *ws, size_t ws_bytes, void *stream);
 
 /* The same sort for the query and the key bucket ids of one attention call in ONE
  * launch (Sec. 3.2 sorts both); outputs as above, one set per side.  The *_sorted_out
@@ -104,7 +113,8 @@ int scfa_sort_by_bucket_pair(const int32_t *bucket_q, const int32_t *bucket_k,
                              int32_t *q_idx_out, int32_t *q_sorted_out, int32_t *q_off_out,
                              uint32_t *q_sort_key_out,
                              int32_t *k_idx_out, int32_t *k_sorted_out, int32_t *k_off_out,
-                             uint32_t *k_sort_key_out, void *stream);
+                             uint32_t *k_sort_key_out,
+                             void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
  * a0. LSH bucketing, the step in front of the hash-sparse path (Sec. 4.2 "Hashing
@@ -132,14 +142,17 @@ int scfa_lsh_buckets(const void *x_q, const void *x_k, const float *R,
  *              the remaining entries = dropped positions, increasing (the order a
  *              stable descending sort of the keep flag gives)
  *   count_out  [S] int32: number of kept tokens
+ *   ws, ws_bytes  (nullable) scratch as for scfa_sort_by_bucket
  */
 int scfa_compact_keep(const uint8_t *keep, int S, int T,
-                      int32_t *idx_out, int32_t *count_out, void *stream);
+                      int32_t *idx_out, int32_t *count_out,
+                      void *ws, size_t ws_bytes, void *stream);
 
 /* Query and key keep flags of one attention call compacted in ONE launch. */
 int scfa_compact_keep_pair(const uint8_t *keep_q, const uint8_t *keep_k, int S, int T,
                            int32_t *q_idx_out, int32_t *n_q_out,
-                           int32_t *k_idx_out, int32_t *n_k_out, void *stream);
+                           int32_t *k_idx_out, int32_t *n_k_out,
+                           void *ws, size_t ws_bytes, void *stream);
 
 /* ------------------------------------------------------------------------
  * a3. Row gather: out[s,r,:] = x[s, idx[s,r], :] for r < n[s], where n[s] =

@@ -30,7 +30,7 @@ EXPORTS = [
     "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv", "scfa_lsh_buckets",
     "scfa_compact_keep", "scfa_q_scale", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
-    "scfa_attn_bwd_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
+    "scfa_attn_bwd_workspace_bytes", "scfa_sort_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
     "scfa_prof_enable", "scfa_prof_reset", "scfa_prof_read", "scfa_prof_occupancy",
 ]
 
@@ -53,11 +53,11 @@ def lib():
         L.scfa_last_hip_error.restype = ci
         L.scfa_error_string.restype = ctypes.c_char_p
         L.scfa_error_string.argtypes = [ci]
-        L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp]
-        L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp]
+        L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp, sz, vp]
         L.scfa_lsh_buckets.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
-        L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp]
-        L.scfa_compact_keep_pair.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp]
+        L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.scfa_compact_keep_pair.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp, sz, vp]
         L.scfa_gather_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
         L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp]
         L.scfa_q_scale.argtypes = [ctypes.c_float]
@@ -70,6 +70,8 @@ def lib():
         L.scfa_qkdrop_attn_fwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, ci, vp, vp, vp, vp]
         L.scfa_attn_bwd_workspace_bytes.argtypes = [ci, ci, ci, ci]
         L.scfa_attn_bwd_workspace_bytes.restype = sz
+        L.scfa_sort_workspace_bytes.argtypes = [ci, ci, ci]
+        L.scfa_sort_workspace_bytes.restype = sz
         L.scfa_hash_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, ci, vp, ci, vp, vp, vp, vp,
                                          ci, ci, ci, ci, ci, cf, ci, vp, vp, vp, vp, sz, vp]
         L.scfa_qkdrop_attn_bwd.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, ci, vp, ci, vp, vp, vp, vp,
@@ -79,7 +81,7 @@ def lib():
         L.scfa_prof_occupancy.argtypes = [ci, ci, ip]
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes", "scfa_q_scale"):
+            if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes", "scfa_sort_workspace_bytes", "scfa_q_scale"):
                 fn.restype = ci
         _lib = L
     return _lib
@@ -144,7 +146,17 @@ def scfa_lsh_buckets(x_q: torch.Tensor, x_k, R: torch.Tensor, H: int, nb: int):
     return (out[0], out[1]) if x_k is not None else out[0]
 
 
-def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int, want_sort_key=False):
+def scfa_sort_workspace_bytes(S, T, nb) -> int:
+    return int(lib().scfa_sort_workspace_bytes(S, T, nb))
+
+
+def _sort_ws(S, T, nb, device, use_ws):
+    """Scratch for the chunked sort of long sequences (None: one workgroup per segment)."""
+    need = scfa_sort_workspace_bytes(S, T, nb) if use_ws else 0
+    return (torch.empty((need,), dtype=torch.uint8, device=device), need) if need else (None, 0)
+
+
+def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int, want_sort_key=False, use_ws=True):
     """bucket [S,T] int32 -> idx [S,T], bucket_sorted [S,T], off [S,nb+1] (all int32); with
     want_sort_key also the [S,T] sort keys bucket << 24 | position (uint32 bits in an int32 tensor)."""
     S, T = bucket.shape
@@ -152,21 +164,24 @@ def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int, want_sort_key=False):
     bsorted = torch.empty_like(bucket)
     off = torch.empty((S, nb + 1), dtype=torch.int32, device=bucket.device)
     key = torch.empty_like(bucket) if want_sort_key else None
-    _check(lib().scfa_sort_by_bucket(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _ptr(key), _stream()),
-           "scfa_sort_by_bucket")
+    ws, ws_bytes = _sort_ws(S, T, nb, bucket.device, use_ws)
+    _check(lib().scfa_sort_by_bucket(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _ptr(key),
+                                     _ptr(ws), ws_bytes, _stream()), "scfa_sort_by_bucket")
     return (idx, bsorted, off, key) if want_sort_key else (idx, bsorted, off)
 
 
-def scfa_compact_keep(keep: torch.Tensor):
+def scfa_compact_keep(keep: torch.Tensor, use_ws=True):
     """keep [S,T] uint8 -> idx [S,T] int32 (kept then dropped positions), count [S] int32."""
     S, T = keep.shape
     idx = torch.empty((S, T), dtype=torch.int32, device=keep.device)
     count = torch.empty((S,), dtype=torch.int32, device=keep.device)
-    _check(lib().scfa_compact_keep(_ptr(keep), S, T, _ptr(idx), _ptr(count), _stream()), "scfa_compact_keep")
+    ws, ws_bytes = _sort_ws(S, T, 2, keep.device, use_ws)
+    _check(lib().scfa_compact_keep(_ptr(keep), S, T, _ptr(idx), _ptr(count), _ptr(ws), ws_bytes, _stream()),
+           "scfa_compact_keep")
     return idx, count
 
 
-def scfa_sort_by_bucket_pair(bucket_q: torch.Tensor, bucket_k: torch.Tensor, nb: int, want_sorted=True):
+def scfa_sort_by_bucket_pair(bucket_q: torch.Tensor, bucket_k: torch.Tensor, nb: int, want_sorted=True, use_ws=True):
     """Both sides of one attention call in one launch ->
     (q_idx, q_sorted, q_off, q_sort_key), (k_idx, k_sorted, k_off, k_sort_key)."""
     S, T = bucket_q.shape
@@ -175,23 +190,25 @@ def scfa_sort_by_bucket_pair(bucket_q: torch.Tensor, bucket_k: torch.Tensor, nb:
     srt = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device) if want_sorted else None
     off = torch.empty((2, S, nb + 1), dtype=torch.int32, device=bucket_q.device)
     key = torch.empty((2, S, T), dtype=torch.int32, device=bucket_q.device)
+    ws, ws_bytes = _sort_ws(S, T, nb, bucket_q.device, use_ws)
     _check(lib().scfa_sort_by_bucket_pair(_ptr(bucket_q), _ptr(bucket_k), S, T, nb, _ptr(both[0]),
                                           _ptr(srt[0]) if want_sorted else None, _ptr(off[0]), _ptr(key[0]),
                                           _ptr(both[1]), _ptr(srt[1]) if want_sorted else None, _ptr(off[1]),
-                                          _ptr(key[1]), _stream()),
+                                          _ptr(key[1]), _ptr(ws), ws_bytes, _stream()),
            "scfa_sort_by_bucket_pair")
     return ((both[0], srt[0] if want_sorted else None, off[0], key[0]),
             (both[1], srt[1] if want_sorted else None, off[1], key[1]))
 
 
-def scfa_compact_keep_pair(keep_q: torch.Tensor, keep_k: torch.Tensor):
+def scfa_compact_keep_pair(keep_q: torch.Tensor, keep_k: torch.Tensor, use_ws=True):
     """Both sides of one attention call in one launch -> (q_idx, n_q), (k_idx, n_k)."""
     S, T = keep_q.shape
     assert keep_k.shape == keep_q.shape
     idx = torch.empty((2, S, T), dtype=torch.int32, device=keep_q.device)
     cnt = torch.empty((2, S), dtype=torch.int32, device=keep_q.device)
+    ws, ws_bytes = _sort_ws(S, T, 2, keep_q.device, use_ws)
     _check(lib().scfa_compact_keep_pair(_ptr(keep_q), _ptr(keep_k), S, T, _ptr(idx[0]), _ptr(cnt[0]), _ptr(idx[1]),
-                                        _ptr(cnt[1]), _stream()), "scfa_compact_keep_pair")
+                                        _ptr(cnt[1]), _ptr(ws), ws_bytes, _stream()), "scfa_compact_keep_pair")
     return (idx[0], cnt[0]), (idx[1], cnt[1])
 
 

@@ -163,41 +163,53 @@ const char* scfa_error_string(int code)
     }
 }
 
+size_t scfa_sort_workspace_bytes(int S, int T, int nb)
+{
+    if (S <= 0 || T <= 0 || nb <= 0 || S > 0x3fffffff) return 0;
+    const size_t one = sort_workspace_bytes(1, S, T, nb < 2 ? 2 : nb), two = sort_workspace_bytes(2, S, T, nb < 2 ? 2 : nb);
+    return align_up(one > two ? one : two, 256);
+}
+
 int scfa_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
-                        int32_t* bucket_sorted_out, int32_t* bucket_off_out, uint32_t* sort_key_out, void* stream)
+                        int32_t* bucket_sorted_out, int32_t* bucket_off_out, uint32_t* sort_key_out,
+                        void* ws, size_t ws_bytes, void* stream)
 {
     if (!bucket || !idx_out || !bucket_off_out || S <= 0 || T <= 0 || nb <= 0) return SCFA_EINVAL;
     if (nb > SCFA_MAX_BUCKETS || S > 0x7fffffff / 1) return SCFA_EUNSUPPORTED;
     if (sort_key_out && T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;
     return launch_sort_by_bucket(1, bucket, nullptr, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, sort_key_out,
-                                 nullptr, nullptr, nullptr, nullptr, (hipStream_t)stream);
+                                 nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, (hipStream_t)stream);
 }
 
 int scfa_sort_by_bucket_pair(const int32_t* bucket_q, const int32_t* bucket_k, int S, int T, int nb,
                              int32_t* q_idx_out, int32_t* q_sorted_out, int32_t* q_off_out, uint32_t* q_sort_key_out,
                              int32_t* k_idx_out, int32_t* k_sorted_out, int32_t* k_off_out, uint32_t* k_sort_key_out,
-                             void* stream)
+                             void* ws, size_t ws_bytes, void* stream)
 {
     if (!bucket_q || !bucket_k || !q_idx_out || !q_off_out || !k_idx_out || !k_off_out || S <= 0 || T <= 0 || nb <= 0)
         return SCFA_EINVAL;
     if (nb > SCFA_MAX_BUCKETS || S > 0x3fffffff) return SCFA_EUNSUPPORTED;
     if ((q_sort_key_out || k_sort_key_out) && T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;
     return launch_sort_by_bucket(2, bucket_q, bucket_k, S, T, nb, q_idx_out, q_sorted_out, q_off_out, q_sort_key_out,
-                                 k_idx_out, k_sorted_out, k_off_out, k_sort_key_out, (hipStream_t)stream);
+                                 k_idx_out, k_sorted_out, k_off_out, k_sort_key_out, ws, ws_bytes, (hipStream_t)stream);
 }
 
-int scfa_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out, void* stream)
+int scfa_compact_keep(const uint8_t* keep, int S, int T, int32_t* idx_out, int32_t* count_out, void* ws,
+                      size_t ws_bytes, void* stream)
 {
     if (!keep || !idx_out || !count_out || S <= 0 || T <= 0) return SCFA_EINVAL;
-    return launch_compact_keep(1, keep, nullptr, S, T, idx_out, count_out, nullptr, nullptr, (hipStream_t)stream);
+    return launch_compact_keep(1, keep, nullptr, S, T, idx_out, count_out, nullptr, nullptr, ws, ws_bytes,
+                               (hipStream_t)stream);
 }
 
 int scfa_compact_keep_pair(const uint8_t* keep_q, const uint8_t* keep_k, int S, int T, int32_t* q_idx_out,
-                           int32_t* n_q_out, int32_t* k_idx_out, int32_t* n_k_out, void* stream)
+                           int32_t* n_q_out, int32_t* k_idx_out, int32_t* n_k_out, void* ws, size_t ws_bytes,
+                           void* stream)
 {
     if (!keep_q || !keep_k || !q_idx_out || !n_q_out || !k_idx_out || !n_k_out || S <= 0 || T <= 0) return SCFA_EINVAL;
     if (S > 0x3fffffff) return SCFA_EUNSUPPORTED;
-    return launch_compact_keep(2, keep_q, keep_k, S, T, q_idx_out, n_q_out, k_idx_out, n_k_out, (hipStream_t)stream);
+    return launch_compact_keep(2, keep_q, keep_k, S, T, q_idx_out, n_q_out, k_idx_out, n_k_out, ws, ws_bytes,
+                               (hipStream_t)stream);
 }
 
 int scfa_lsh_buckets(const void* x_q, const void* x_k, const float* R, int S, int H, int T, int d, int nb, int dtype,

@@ -61,9 +61,10 @@ constexpr int F32_TILE_N = 32;
 // ---- kernel launchers (defined in the .hip files) ---------------------------
 int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
                           int32_t* idx0, int32_t* sorted0, int32_t* off0, uint32_t* key0, int32_t* idx1,
-                          int32_t* sorted1, int32_t* off1, uint32_t* key1, hipStream_t st);
+                          int32_t* sorted1, int32_t* off1, uint32_t* key1, void* ws, size_t ws_bytes, hipStream_t st);
 int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
-                        int32_t* count0, int32_t* idx1, int32_t* count1, hipStream_t st);
+                        int32_t* count0, int32_t* idx1, int32_t* count1, void* ws, size_t ws_bytes, hipStream_t st);
+size_t sort_workspace_bytes(int n_problems, int S, int T, int nb);
 int launch_lsh_buckets(int n_problems, const void* x0, const void* x1, const float* R, int S, int H, int T, int d,
                        int nb, bool bf16, int32_t* out0, int32_t* out1, hipStream_t st);
 int launch_gather_rows(int n_tensors, const void* const* x, const int32_t* const* idx, const int32_t* const* count,

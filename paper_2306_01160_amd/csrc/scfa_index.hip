@@ -41,15 +41,43 @@ struct SortProblem {
 
 constexpr int SORT_PREFETCH = 16;  // 64-token steps whose keys are loaded together
 
+// Long sequences in few segments leave most of the chip idle with one workgroup per segment, so a
+// segment can be cut into n_chunks runs of chunk_len tokens (a multiple of 64 * SORT_WAVES), one
+// workgroup each: a first kernel counts the keys of every chunk, the sort kernel then starts each
+// key of its chunk after all smaller keys of the segment and after the same key in earlier chunks.
+constexpr int COUNT_THREADS = 256;
+
+template <bool KEEP_MODE>
+__global__ __launch_bounds__(COUNT_THREADS) void sort_chunk_count_kernel(
+    const void* keys0, const void* keys1, int S, int T, int nb, int n_chunks, int chunk_len,
+    int32_t* __restrict__ chunk_counts /* [problem][S][n_chunks][nb] */)
+{
+    extern __shared__ int32_t smem[];
+    const int c = blockIdx.x % n_chunks;
+    const int ps = blockIdx.x / n_chunks;       // problem * S + segment
+    const void* __restrict__ keys = ps >= S ? keys1 : keys0;
+    const size_t seg = (size_t)(ps >= S ? ps - S : ps) * T;
+    for (int k = threadIdx.x; k < nb; k += COUNT_THREADS) smem[k] = 0;
+    __syncthreads();
+    const int t0 = c * chunk_len, t1 = min(T, t0 + chunk_len);
+    for (int t = t0 + threadIdx.x; t < t1; t += COUNT_THREADS) atomicAdd(&smem[load_key<KEEP_MODE>(keys, seg + t, nb)], 1);
+    __syncthreads();
+    for (int k = threadIdx.x; k < nb; k += COUNT_THREADS) chunk_counts[((size_t)ps * n_chunks + c) * nb + k] = smem[k];
+}
+
 template <bool KEEP_MODE>
 __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
-    SortProblem p0, SortProblem p1, int S, int T, int nb, int nbits)
+    SortProblem p0, SortProblem p1, int S, int T, int nb, int nbits, int n_chunks, int chunk_len,
+    const int32_t* __restrict__ chunk_counts)
 {
     extern __shared__ int32_t smem[];
     int32_t* hist = smem;                       // [SORT_WAVES][nb]  counts, then running bases
     int32_t* tot = smem + SORT_WAVES * nb;      // [nb+1]
-    const bool second = (int)blockIdx.x >= S;
-    const int s = second ? blockIdx.x - S : blockIdx.x;
+    int32_t* before = tot + nb + 1;             // [nb] tokens of the key in earlier chunks of the segment
+    const int chunk = blockIdx.x % n_chunks;
+    const int ps = blockIdx.x / n_chunks;
+    const bool second = ps >= S;
+    const int s = second ? ps - S : ps;
     const void* __restrict__ keys = second ? p1.keys : p0.keys;
     int32_t* __restrict__ idx_out = second ? p1.idx_out : p0.idx_out;
     int32_t* __restrict__ key_sorted_out = second ? p1.key_sorted_out : p0.key_sorted_out;
@@ -59,11 +87,12 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
     const int lane = threadIdx.x & 63;
     const size_t seg = (size_t)s * T;
 
-    // contiguous run of this wavefront, a multiple of 64 tokens
-    int run = (T + SORT_WAVES - 1) / SORT_WAVES;
+    // contiguous run of this wavefront inside the workgroup's chunk, a multiple of 64 tokens
+    const int c0 = chunk * chunk_len, c1 = min(T, c0 + chunk_len);
+    int run = (c1 - c0 + SORT_WAVES - 1) / SORT_WAVES;
     run = (run + 63) & ~63;
-    const int r0 = min(wave * run, T);
-    const int r1 = min(r0 + run, T);
+    const int r0 = min(c0 + wave * run, c1);
+    const int r1 = min(r0 + run, c1);
 
     for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] = 0;
     __syncthreads();
@@ -84,7 +113,7 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
     }
     __syncthreads();
 
-    // per key: exclusive prefix over wavefronts (in place) and the key total
+    // per key: exclusive prefix over wavefronts (in place) and the key total of the segment
     for (int k = threadIdx.x; k < nb; k += SORT_THREADS) {
         int acc = 0;
         for (int w = 0; w < SORT_WAVES; ++w) {
@@ -92,6 +121,16 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
             hist[w * nb + k] = acc;
             acc += c;
         }
+        int earlier = 0;
+        if (n_chunks > 1) {   // the segment's total and the part of it that lies in earlier chunks
+            const int32_t* cc = chunk_counts + (size_t)ps * n_chunks * nb + k;
+            acc = 0;
+            for (int c = 0; c < n_chunks; ++c) {
+                if (c == chunk) earlier = acc;
+                acc += cc[(size_t)c * nb];
+            }
+        }
+        before[k] = earlier;
         tot[k] = acc;
     }
     __syncthreads();
@@ -105,12 +144,14 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
         tot[nb] = acc;
     }
     __syncthreads();
-    if (KEEP_MODE) {
-        if (threadIdx.x == 0) off_out[s] = tot[1];
-    } else {
-        for (int k = threadIdx.x; k <= nb; k += SORT_THREADS) off_out[(size_t)s * (nb + 1) + k] = tot[k];
+    if (chunk == 0) {
+        if (KEEP_MODE) {
+            if (threadIdx.x == 0) off_out[s] = tot[1];
+        } else {
+            for (int k = threadIdx.x; k <= nb; k += SORT_THREADS) off_out[(size_t)s * (nb + 1) + k] = tot[k];
+        }
     }
-    for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] += tot[i % nb];
+    for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] += tot[i % nb] + before[i % nb];
     __syncthreads();
 
     // rank and scatter, 64 consecutive tokens per step, keys again loaded a group at a time
@@ -153,32 +194,64 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
 }
 
 // n_problems: 1 or 2 (bucket1 etc. ignored for 1)
-int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
-                          int32_t* idx0, int32_t* sorted0, int32_t* off0, uint32_t* key0, int32_t* idx1,
-                          int32_t* sorted1, int32_t* off1, uint32_t* key1, hipStream_t st)
+// Chunks per segment for n_wg = segments x problems workgroups: enough to fill the chip once, but
+// chunks of at least 4096 tokens; 1 for short sequences.  Host arithmetic; the workspace query and
+// the launchers must agree.
+int sort_chunks(int n_wg, int T)
 {
-    int nbits = 0;
-    while ((1 << nbits) < nb) ++nbits;
-    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
-    const SortProblem p0{bucket0, idx0, sorted0, off0, key0}, p1{bucket1, idx1, sorted1, off1, key1};
-    ProfScope prof(SCFA_K_SORT, st);
-    hipLaunchKernelGGL(stable_sort_small_keys_kernel<false>, dim3(S * n_problems), dim3(SORT_THREADS), smem, st,
-                       p0, p1, S, T, nb, nbits);
+    if (T < 8192) return 1;
+    int c = (256 + n_wg - 1) / n_wg;
+    if (c > T / 4096) c = T / 4096;
+    if (c > 64) c = 64;
+    return c < 1 ? 1 : c;
+}
+
+static int sort_chunk_len(int T, int n_chunks)
+{
+    const int unit = 64 * SORT_WAVES;
+    return ((T + n_chunks - 1) / n_chunks + unit - 1) / unit * unit;
+}
+
+size_t sort_workspace_bytes(int n_problems, int S, int T, int nb)
+{
+    const int c = sort_chunks(S * n_problems, T);
+    return c > 1 ? sizeof(int32_t) * (size_t)n_problems * S * c * nb : 0;
+}
+
+template <bool KEEP_MODE>
+static int launch_sort_t(int kid, int n_problems, const SortProblem& p0, const SortProblem& p1, int S, int T, int nb,
+                         int nbits, void* ws, size_t ws_bytes, hipStream_t st)
+{
+    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + 2 * (size_t)nb + 1);
+    int n_chunks = sort_chunks(S * n_problems, T);
+    if (!ws || ws_bytes < sort_workspace_bytes(n_problems, S, T, nb)) n_chunks = 1;   // no scratch: one workgroup per segment
+    int chunk_len = sort_chunk_len(T, n_chunks);
+    n_chunks = (T + chunk_len - 1) / chunk_len;      // rounding the length up may leave fewer chunks
+    ProfScope prof(kid, st);
+    if (n_chunks > 1)
+        hipLaunchKernelGGL(sort_chunk_count_kernel<KEEP_MODE>, dim3(S * n_problems * n_chunks), dim3(COUNT_THREADS),
+                           sizeof(int32_t) * nb, st, p0.keys, p1.keys, S, T, nb, n_chunks, chunk_len, (int32_t*)ws);
+    hipLaunchKernelGGL(stable_sort_small_keys_kernel<KEEP_MODE>, dim3(S * n_problems * n_chunks), dim3(SORT_THREADS), smem,
+                       st, p0, p1, S, T, nb, nbits, n_chunks, chunk_len, (const int32_t*)ws);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
 
-int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
-                        int32_t* count0, int32_t* idx1, int32_t* count1, hipStream_t st)
+int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
+                          int32_t* idx0, int32_t* sorted0, int32_t* off0, uint32_t* key0, int32_t* idx1,
+                          int32_t* sorted1, int32_t* off1, uint32_t* key1, void* ws, size_t ws_bytes, hipStream_t st)
 {
-    const int nb = 2;
-    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + nb + 1);
+    int nbits = 0;
+    while ((1 << nbits) < nb) ++nbits;
+    const SortProblem p0{bucket0, idx0, sorted0, off0, key0}, p1{bucket1, idx1, sorted1, off1, key1};
+    return launch_sort_t<false>(SCFA_K_SORT, n_problems, p0, p1, S, T, nb, nbits, ws, ws_bytes, st);
+}
+
+int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
+                        int32_t* count0, int32_t* idx1, int32_t* count1, void* ws, size_t ws_bytes, hipStream_t st)
+{
     const SortProblem p0{keep0, idx0, nullptr, count0, nullptr}, p1{keep1, idx1, nullptr, count1, nullptr};
-    ProfScope prof(SCFA_K_COMPACT, st);
-    hipLaunchKernelGGL(stable_sort_small_keys_kernel<true>, dim3(S * n_problems), dim3(SORT_THREADS), smem, st,
-                       p0, p1, S, T, nb, 1);
-    SCFA_HIP_TRY(hipGetLastError());
-    return SCFA_OK;
+    return launch_sort_t<true>(SCFA_K_COMPACT, n_problems, p0, p1, S, T, 2, 1, ws, ws_bytes, st);
 }
 
 // ---------------------------------------------------------------------------

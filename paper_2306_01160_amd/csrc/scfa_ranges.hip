@@ -24,7 +24,9 @@
 //
 // One workgroup builds one list of one segment (the forward and the backward list are
 // independent).  The index vector that is searched is first copied into LDS when it fits,
-// so the dependent steps of the binary searches cost LDS, not global-memory, latency.
+// so the dependent steps of the binary searches cost LDS, not global-memory, latency; when it
+// does not fit, every 2^shift-th entry is copied and a search ends with <= shift steps in global
+// memory.
 #include "scfa_common.hpp"
 
 namespace scfa {
@@ -53,6 +55,24 @@ __device__ __forceinline__ int count_lt(const int32_t* __restrict__ a, int n, in
     return lo;
 }
 
+// The searched vector: `g` in global memory and lds[i] = g[i << shift] (shift 0: all of it).
+struct Searched { const int32_t* g; const int32_t* lds; int shift; };
+
+// number of entries of g[begin, begin + n) that are <= v (LE) or < v
+template <bool LE>
+__device__ __forceinline__ int count_in(const Searched& a, int begin, int n, int v)
+{
+    if (a.shift == 0) return LE ? count_le(a.lds + begin, n, v) : count_lt(a.lds + begin, n, v);
+    int lo = begin, hi = begin + n;                        // the answer is a position in [lo, hi]
+    const int j0 = (begin + (1 << a.shift) - 1) >> a.shift, j1 = (begin + n - 1) >> a.shift;   // samples inside
+    if (n > 0 && j0 <= j1) {
+        const int c = LE ? count_le(a.lds + j0, j1 - j0 + 1, v) : count_lt(a.lds + j0, j1 - j0 + 1, v);
+        if (c > 0) lo = ((j0 + c - 1) << a.shift) + 1;     // that sample and all before it count
+        if (c <= j1 - j0) hi = (j0 + c) << a.shift;        // the next sample does not
+    }
+    return lo - begin + (LE ? count_le(a.g + lo, hi - lo, v) : count_lt(a.g + lo, hi - lo, v));
+}
+
 constexpr int ORDER_GROUP = 2;   // buckets whose items are dispatched together
 
 struct Item { int a_begin, a_count, b_begin, b_count, b_extra, bucket, n_buckets; };
@@ -70,7 +90,7 @@ __device__ __forceinline__ int order_key(int bucket, int b_count)
 // STRICT (a key is visible only to later positions, App. B.1's ">" in place of ">="): the
 // comparisons with equality swap sides, <= becomes < and >= becomes >.
 template <bool FORWARD, bool STRICT>
-__device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_idx,
+__device__ void build_list(const int32_t* __restrict__ a_idx, const Searched& b_idx,
                            const int32_t* a_off, const int32_t* b_off, int nb, int tile_a,
                            int tile_b, int n_items_max, int32_t* __restrict__ work_out,
                            long long* counters2, int32_t* s_tile_base, int32_t* s_unit_first, int32_t* s_cost)
@@ -133,13 +153,13 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_i
         const int bb = b_off[b], bn = b_off[b + 1] - b_off[b];
         if (FORWARD) {
             it.b_begin = bb;
-            it.b_count = STRICT ? count_lt(b_idx + bb, bn, pos_max) : count_le(b_idx + bb, bn, pos_max);
-            it.b_extra = STRICT ? count_lt(b_idx + bb, bn, pos_min) : count_le(b_idx + bb, bn, pos_min);
+            it.b_count = count_in<!STRICT>(b_idx, bb, bn, pos_max);
+            it.b_extra = count_in<!STRICT>(b_idx, bb, bn, pos_min);
         } else {
-            const int first = STRICT ? count_le(b_idx + bb, bn, pos_min) : count_lt(b_idx + bb, bn, pos_min);
+            const int first = count_in<STRICT>(b_idx, bb, bn, pos_min);
             it.b_begin = bb + first;
             it.b_count = bn - first;
-            it.b_extra = (STRICT ? count_le(b_idx + bb, bn, pos_max) : count_lt(b_idx + bb, bn, pos_max)) - first;
+            it.b_extra = count_in<STRICT>(b_idx, bb, bn, pos_max) - first;
             if (it.b_extra < 0) it.b_extra = 0;
         }
         return it;
@@ -191,7 +211,7 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const int32_t* b_i
 __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     int variant, const int32_t* __restrict__ q_idx, const int32_t* __restrict__ k_idx,
     const int32_t* __restrict__ q_off_g, const int32_t* __restrict__ k_off_g, int T, int nb,
-    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int stage_in_lds, int strict,
+    int fwd_m, int fwd_n, int bwd_n, int bwd_m, int n_fwd, int n_bwd, int stage_shift, int strict,
     int32_t* __restrict__ fwd_work, int32_t* __restrict__ bwd_work, long long* __restrict__ counters)
 {
     extern __shared__ int32_t smem[];
@@ -217,10 +237,10 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
     }
     const int32_t* qi = q_idx + (size_t)s * T;
     const int32_t* ki = k_idx + (size_t)s * T;
-    const int32_t* searched = backward ? qi : ki;     // the ranged side
-    if (stage_in_lds) {   // 16-byte loads, eight in flight per thread (the segment base is 16-byte aligned when T % 4 == 0)
+    const int32_t* searched_g = backward ? qi : ki;    // the ranged side
+    if (stage_shift == 0) {   // 16-byte loads, eight in flight per thread (the segment base is 16-byte aligned when T % 4 == 0)
         if ((T & 3) == 0) {
-            const int4* src4 = reinterpret_cast<const int4*>(searched);
+            const int4* src4 = reinterpret_cast<const int4*>(searched_g);
             int4* dst4 = reinterpret_cast<int4*>(s_idx);
             const int n4 = T >> 2;
             for (int t0 = 0; t0 < n4; t0 += RANGES_THREADS * 8) {
@@ -237,10 +257,13 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
                 }
             }
         } else {
-            for (int t = threadIdx.x; t < T; t += RANGES_THREADS) s_idx[t] = searched[t];
+            for (int t = threadIdx.x; t < T; t += RANGES_THREADS) s_idx[t] = searched_g[t];
         }
-        searched = s_idx;
+    } else {                  // every 2^shift-th entry
+        const int n_s = ((T - 1) >> stage_shift) + 1;
+        for (int i = threadIdx.x; i < n_s; i += RANGES_THREADS) s_idx[i] = searched_g[(size_t)i << stage_shift];
     }
+    const Searched searched{searched_g, s_idx, stage_shift};
     __syncthreads();
     long long* cnt = counters ? counters + (size_t)s * 4 : nullptr;
     int32_t* fw = fwd_work + (size_t)s * n_fwd * WORK_STRIDE;
@@ -263,8 +286,9 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
 {
     const int n_max = n_fwd > n_bwd ? n_fwd : n_bwd;
     const size_t small = sizeof(int32_t) * ((4 * (size_t)(nb + 1) + (size_t)n_max + 3) & ~(size_t)3);
-    const int stage = small + sizeof(int32_t) * (size_t)T <= 144 * 1024 ? 1 : 0;
-    const size_t smem = small + (stage ? sizeof(int32_t) * (size_t)T : 0);
+    int shift = 0;            // the searched vector is staged in LDS whole, or every 2^shift-th entry of it
+    while (small + sizeof(int32_t) * ((((size_t)T - 1) >> shift) + 1) > 144 * 1024) ++shift;
+    const size_t smem = small + sizeof(int32_t) * ((((size_t)T - 1) >> shift) + 1);
     static bool attr_set = false;
     if (!attr_set) {
         SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&block_ranges_kernel),
@@ -273,7 +297,7 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
     }
     ProfScope prof(SCFA_K_RANGES, st);
     hipLaunchKernelGGL(block_ranges_kernel, dim3(S, bwd_work ? 2 : 1), dim3(RANGES_THREADS), smem, st, variant, q_idx,
-                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, stage, strict, fwd_work,
+                       k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, shift, strict, fwd_work,
                        bwd_work, (long long*)counters);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;

@@ -38,18 +38,21 @@ def test_host_only_entry_points():
 def test_argument_checks_reject_before_any_launch():
     """Null pointers / bad sizes return error codes from the host-side checks."""
     L = binding.lib()
-    assert L.scfa_sort_by_bucket(None, 1, 8, 2, None, None, None, None, None) == binding.SCFA_EINVAL
-    assert L.scfa_compact_keep(None, 1, 8, None, None, None) == binding.SCFA_EINVAL
+    assert L.scfa_sort_by_bucket(None, 1, 8, 2, None, None, None, None, None, 0, None) == binding.SCFA_EINVAL
+    assert L.scfa_compact_keep(None, 1, 8, None, None, None, 0, None) == binding.SCFA_EINVAL
     assert L.scfa_gather_rows(None, None, None, 1, 8, 64, 0, 0, 1.0, None, None) == binding.SCFA_EINVAL
     one = ctypes.c_void_p(16)   # never dereferenced: checks fail first
-    assert L.scfa_sort_by_bucket(one, 1, 8, 100000, one, one, one, None, None) == binding.SCFA_EUNSUPPORTED
-    assert L.scfa_sort_by_bucket(one, 0, 8, 2, one, one, one, None, None) == binding.SCFA_EINVAL
-    assert L.scfa_sort_by_bucket(one, 1, 1 << 24, 2, one, one, one, one, None) == binding.SCFA_EUNSUPPORTED   # position does not fit a sort key
+    assert L.scfa_sort_by_bucket(one, 1, 8, 100000, one, one, one, None, None, 0, None) == binding.SCFA_EUNSUPPORTED
+    assert L.scfa_sort_by_bucket(one, 0, 8, 2, one, one, one, None, None, 0, None) == binding.SCFA_EINVAL
+    assert L.scfa_sort_by_bucket(one, 1, 1 << 24, 2, one, one, one, one, None, 0, None) == binding.SCFA_EUNSUPPORTED   # position does not fit a sort key
     assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 1 << 24, 64, 0, 0.125, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_gather_rows(one, one, None, 1, 8, 3, 0, 0, 1.0, one, None) == binding.SCFA_EINVAL      # 6-byte rows
     assert L.scfa_gather_rows(one, one, None, 1, 8, 64, 7, 7, 1.0, one, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_gather_rows(one, one, None, 1, 8, 64, 1, 2, 1.0, one, None) == binding.SCFA_EUNSUPPORTED   # fp32 -> fp16
     assert L.scfa_gather_rows(one, one, None, 1, 8, 64, 0, 0, 0.5, one, None) == binding.SCFA_EUNSUPPORTED   # scaled bf16 -> bf16
+    assert binding.scfa_sort_workspace_bytes(4, 1024, 8) == 0          # short sequences: one workgroup per segment
+    assert binding.scfa_sort_workspace_bytes(24, 16384, 8) >= 2 * 24 * 4 * 8 * 4   # 4 chunks, two sides
+    assert binding.scfa_sort_workspace_bytes(0, 16384, 8) == 0
     assert abs(binding.scfa_q_scale(0.125) - 0.125 * 1.4426950408889634) < 1e-7
     assert L.scfa_block_ranges(1, one, one, one, one, 1, 8, 2, 128, 64, 128, 64, 0, one, one, None, None) == binding.SCFA_EINVAL
     assert L.scfa_block_ranges(0, one, one, one, one, 1, 8, 2, 100, 64, 128, 64, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED

@@ -163,6 +163,35 @@ def test_pair_entry_points_match_single_calls(S, T, nb):
             assert torch.equal(g_k[s_, :b], r_k[s_, :b]) and torch.equal(g_v[s_, :b], r_v[s_, :b])
 
 
+@pytest.mark.parametrize("S,T,nb", [(1, 65536, 16), (3, 20000, 256), (2, 8192, 1), (1, 32768 + 77, 7), (40, 8192, 8)])
+def test_chunked_sort_equals_single_workgroup_sort(S, T, nb):
+    """Long sequences are cut into chunks sorted by several workgroups when scratch is given: same
+    bits as the one-workgroup-per-segment kernel and as the oracle, for the sort and the compaction."""
+    rng = np.random.default_rng(S * 7 + T + nb)
+    b = rng.integers(0, nb, (S, T)).astype(np.int32)
+    b[0, : T // 3] = nb - 1                          # a long run of one key across chunk borders
+    assert sc.scfa_sort_workspace_bytes(S, T, nb) > 0 or S * 2 >= 256
+    a = sc.scfa_sort_by_bucket(_t(b), nb, want_sort_key=True, use_ws=True)
+    c = sc.scfa_sort_by_bucket(_t(b), nb, want_sort_key=True, use_ws=False)
+    for x, y in zip(a, c):
+        assert torch.equal(x, y)
+    ref = oracle.sort_by_bucket(b, nb)
+    for x, r in zip(a[:3], ref):
+        assert np.array_equal(x.cpu().numpy(), r)
+    (qa, _, oa, ka), (qb, _, ob, kb) = sc.scfa_sort_by_bucket_pair(_t(b), _t(b[:, ::-1].copy()), nb, want_sorted=False)
+    (qc, _, oc, kc), (qd, _, od, kd) = sc.scfa_sort_by_bucket_pair(_t(b), _t(b[:, ::-1].copy()), nb, want_sorted=False, use_ws=False)
+    assert torch.equal(qa, qc) and torch.equal(qb, qd) and torch.equal(oa, oc) and torch.equal(ob, od)
+    assert torch.equal(ka, kc) and torch.equal(kb, kd) and torch.equal(qa, a[0])
+    keep = (rng.random((S, T)) < 0.4).astype(np.uint8)
+    i1, n1 = sc.scfa_compact_keep(_t(keep), use_ws=True)
+    i2, n2 = sc.scfa_compact_keep(_t(keep), use_ws=False)
+    ri, rn = oracle.compact_keep(keep)
+    assert torch.equal(i1, i2) and torch.equal(n1, n2)
+    assert np.array_equal(n1.cpu().numpy(), rn)
+    for s_ in range(S):
+        assert np.array_equal(i1[s_, : rn[s_]].cpu().numpy(), ri[s_, : rn[s_]])
+
+
 # ------------------------------------------------------------------ LSH bucketing
 
 @pytest.mark.parametrize("S,H,T,d,nb,dtype", [(4, 2, 1000, 64, 8, torch.bfloat16), (3, 3, 777, 128, 16, torch.bfloat16),
@@ -333,6 +362,39 @@ def test_schedule_strict_causal(S, T, nb):
     _check_schedule(sc.SCFA_HASH, bq, bq, nb, tiles, strict=True)
     kq = (rng.random((S, T)) < 0.5).astype(np.uint8)
     _check_schedule(sc.SCFA_QKDROP, kq, kq, 1, tiles, strict=True)
+
+
+@pytest.mark.parametrize("T,nb,strict", [(50001, 16, False), (70000, 5, True), (300000, 3, False)])
+def test_schedule_long_sequences(T, nb, strict):
+    """Sequences whose index vector does not fit in LDS are searched in two levels (every 2^k-th
+    entry in LDS, then a few steps in global memory): every range end of every single-bucket item
+    must equal what numpy's searchsorted gives on the oracle's sorted index vectors."""
+    rng = np.random.default_rng(T)
+    S = 2
+    bq = rng.integers(0, nb, (S, T)).astype(np.int32); bk = rng.integers(0, nb, (S, T)).astype(np.int32)
+    fm, fn, bn, bm = tiles = sc.scfa_tile_config(64, sc.SCFA_BF16)
+    q_idx, _, q_off = sc.scfa_sort_by_bucket(_t(bq), nb)
+    k_idx, _, k_off = sc.scfa_sort_by_bucket(_t(bk), nb)
+    fwd, bwd, cnt = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
+                                         flags=sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0)
+    fwd, bwd = fwd.cpu().numpy(), bwd.cpu().numpy()
+    qi, ki, qo, ko = (a.cpu().numpy() for a in (q_idx, k_idx, q_off, k_off))
+    le, lt = ("left", "right") if strict else ("right", "left")     # searchsorted side for "<=" and "<" (swapped when strict)
+    for s in range(S):
+        live = fwd[s][fwd[s][:, 1] > 0]
+        assert live[:, 1].sum() == T and (live[:, 6] == 1).all()
+        for qb, qc, kb, kc, kn, b, _, _ in live:
+            keys = ki[s, ko[s, b]:ko[s, b + 1]]
+            assert kb == ko[s, b]
+            assert kc == np.searchsorted(keys, qi[s, qb + qc - 1], side=le)
+            assert kn == np.searchsorted(keys, qi[s, qb], side=le)
+        live = bwd[s][bwd[s][:, 1] > 0]
+        assert live[:, 1].sum() == T
+        for kb, kc, qb, qc, qm, b, _, _ in live:
+            qs = qi[s, qo[s, b]:qo[s, b + 1]]
+            first = np.searchsorted(qs, ki[s, kb], side=lt)
+            assert qb == qo[s, b] + first and qc == len(qs) - first
+            assert qm == max(0, np.searchsorted(qs, ki[s, kb + kc - 1], side=lt) - first)
 
 
 def test_schedule_regular_case_is_lower_triangular():
