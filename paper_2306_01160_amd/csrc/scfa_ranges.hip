@@ -165,19 +165,52 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const Searched& b_
         return it;
     };
 
-    for (int w = threadIdx.x; w < n_items; w += RANGES_THREADS) {
+    // the first KEEP items of a thread stay in registers between the two passes (their range
+    // ends cost dependent memory reads); beyond that they are computed again
+    constexpr int KEEP = 4;
+    Item kept[KEEP];
+#pragma unroll
+    for (int j = 0; j < KEEP; ++j) {
+        const int w = threadIdx.x + j * RANGES_THREADS;
+        if (w < n_items) {
+            kept[j] = make_item(w);
+            s_cost[w] = order_key(kept[j].bucket, kept[j].b_count);
+        }
+    }
+    for (int w = threadIdx.x + KEEP * RANGES_THREADS; w < n_items; w += RANGES_THREADS) {
         const Item it = make_item(w);
         s_cost[w] = order_key(it.bucket, it.b_count);
     }
     __syncthreads();
 
     long long tiles = 0, rect = 0;
-    for (int w = threadIdx.x; w < n_items_max; w += RANGES_THREADS) {
+    for (int w = threadIdx.x, j = 0; w < n_items_max; w += RANGES_THREADS, ++j) {
         if (w < n_items) {
-            const Item it = make_item(w);
+            Item it;
+            if (j < KEEP) {
+                it = kept[0];
+#pragma unroll
+                for (int u = 1; u < KEEP; ++u) if (j == u) it = kept[u];
+            } else {
+                it = make_item(w);
+            }
             const int c = order_key(it.bucket, it.b_count);
-            int rank = 0;
-            for (int u = 0; u < n_items; ++u) {
+            // items are generated in bucket order, so those of one bucket pair are a run [lo, hi) of w
+            // (binary searches on the pair field); only they have to be compared
+            const int pair = c >> 24;
+            int lo = 0, hi = w;                      // first item of the pair: in [0, w]
+            while (lo < hi) {
+                const int m = (lo + hi) >> 1;
+                if ((s_cost[m] >> 24) < pair) lo = m + 1; else hi = m;
+            }
+            int e0 = w + 1, e1 = n_items;            // first item after the pair: in [w + 1, n_items]
+            while (e0 < e1) {
+                const int m = (e0 + e1) >> 1;
+                if ((s_cost[m] >> 24) > pair) e1 = m; else e0 = m + 1;
+            }
+            hi = e0;
+            int rank = lo;
+            for (int u = lo; u < hi; ++u) {
                 const int cu = s_cost[u];
                 rank += (cu < c) || (cu == c && u < w);
             }
@@ -261,7 +294,19 @@ __global__ __launch_bounds__(RANGES_THREADS) void block_ranges_kernel(
         }
     } else {                  // every 2^shift-th entry
         const int n_s = ((T - 1) >> stage_shift) + 1;
-        for (int i = threadIdx.x; i < n_s; i += RANGES_THREADS) s_idx[i] = searched_g[(size_t)i << stage_shift];
+        for (int i0 = 0; i0 < n_s; i0 += RANGES_THREADS * 8) {   // eight loads in flight per thread
+            int32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * RANGES_THREADS + threadIdx.x;
+                v[u] = i < n_s ? searched_g[(size_t)i << stage_shift] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * RANGES_THREADS + threadIdx.x;
+                if (i < n_s) s_idx[i] = v[u];
+            }
+        }
     }
     const Searched searched{searched_g, s_idx, stage_shift};
     __syncthreads();
