@@ -169,17 +169,11 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const Searched& b_
     // ends cost dependent memory reads); beyond that they are computed again
     constexpr int KEEP = 4;
     Item kept[KEEP];
-#pragma unroll
-    for (int j = 0; j < KEEP; ++j) {
-        const int w = threadIdx.x + j * RANGES_THREADS;
-        if (w < n_items) {
-            kept[j] = make_item(w);
-            s_cost[w] = order_key(kept[j].bucket, kept[j].b_count);
-        }
-    }
-    for (int w = threadIdx.x + KEEP * RANGES_THREADS; w < n_items; w += RANGES_THREADS) {
+    for (int w = threadIdx.x, j = 0; w < n_items; w += RANGES_THREADS, ++j) {
         const Item it = make_item(w);
         s_cost[w] = order_key(it.bucket, it.b_count);
+#pragma unroll
+        for (int u = 0; u < KEEP; ++u) if (j == u) kept[u] = it;   // register selects, no indexing
     }
     __syncthreads();
 
