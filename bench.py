@@ -39,7 +39,8 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 / fp16 MFMA peak (published)
 def measured_traffic(kernel, workload="c4"):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of `workload`
     (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy of known size); None if no summary covers it."""
-    name = {"c4": "scfa_hot_path_config4_hash_T16384.md", "c5": "scfa_hot_path_config5_qkdrop_T32768_d128.md"}.get(workload)
+    name = {"c4": "scfa_hot_path_config4_hash_T16384.md", "c5": "scfa_hot_path_config5_qkdrop_T32768_d128.md",
+            "c3": "scfa_hot_path_config3_hash_T8192_nb16.md"}.get(workload)
     if name is None:
         return None
     path = os.path.join(ROOT, "profiles", name)
