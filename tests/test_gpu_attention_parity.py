@@ -172,6 +172,29 @@ def test_bucket_present_in_q_but_absent_in_k_gives_zero_rows():
     assert_within(errs, wl.dtype)
 
 
+def test_queries_and_keys_in_disjoint_buckets():
+    """No query shares a bucket with any key: every output row is zero, every LSE is -inf, every
+    gradient is zero (large and small buckets, i.e. own and shared work items)."""
+    for T, nb in ((900, 4), (700, 64)):
+        wl = W.hash_uniform(43, 1, 2, T, 64, nb)
+        wl.lab_q[...] = (wl.lab_q // 2) * 2            # queries in even buckets
+        wl.lab_k[...] = (wl.lab_k // 2) * 2 + 1        # keys in odd buckets
+        o, lse, grads, _ = run_gpu(wl)
+        assert not o.float().cpu().numpy().any()
+        assert np.isneginf(lse.cpu().numpy()).all()
+        for g in grads:
+            assert not g.cpu().numpy().any()
+
+
+def test_more_buckets_than_tokens():
+    """256 buckets for 100 tokens: most buckets are empty, the rest hold one or two rows."""
+    wl = W.hash_uniform(44, 2, 2, 100, 128, 256)
+    wl.lab_k[...] = wl.lab_q                          # shared labels so that some pairs exist
+    _full_check(wl)
+    wl.meta["strict"] = True
+    _full_check(wl)
+
+
 def test_zero_kept_keys_and_zero_kept_queries():
     wl = W.qkdrop_bernoulli(42, 1, 2, 300, 64, 0.5, 0.5)
     wl.lab_k[0, 0, :] = 0                # head 0: every key dropped
