@@ -64,3 +64,30 @@ def test_argument_checks_reject_before_any_launch():
                                 one, one, one, ws, 16, None) == binding.SCFA_EWORKSPACE
     assert L.scfa_hash_attn_bwd(one, one, one, one, one, one, 1, one, 1, one, None, one, one, 1, 1, 8, 64, 1, 0.125, 0,
                                 one, one, one, ws, 1 << 20, None) == binding.SCFA_EUNSUPPORTED
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: `bench.py --gpus N` with N > 1 exits with a message and measures nothing."""
+    import subprocess, sys
+    bench = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py")
+    r = subprocess.run([sys.executable, bench, "--gpus", "2", "--steps", "1"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in (r.stderr + r.stdout)
+    assert '"metric"' not in r.stdout
+
+
+def test_count_allowed_pairs_matches_the_mask():
+    """bench.py's pair count (searchsorted per bucket) equals the sum of the oracle's mask, for buckets and keep flags."""
+    import importlib.util
+    import numpy as np
+    import oracle
+    spec = importlib.util.spec_from_file_location(
+        "bench", os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "bench.py"))
+    bench = importlib.util.module_from_spec(spec); spec.loader.exec_module(bench)
+    rng = np.random.default_rng(0)
+    lq = rng.integers(0, 5, (3, 200)).astype(np.int32); lk = rng.integers(0, 5, (3, 200)).astype(np.int32)
+    want = sum(int(oracle.allowed_mask(lq[s], lk[s], oracle.HASH).sum()) for s in range(3))
+    assert bench.count_allowed_pairs(lq, lk, 5) == want
+    kq = (rng.random((3, 200)) < 0.5).astype(np.uint8); kk = (rng.random((3, 200)) < 0.3).astype(np.uint8)
+    want = sum(int(oracle.allowed_mask(kq[s], kk[s], oracle.QKDROP).sum()) for s in range(3))
+    assert bench.count_allowed_pairs(kq, kk, 1, keep_flags=True) == want
