@@ -167,20 +167,17 @@ int scfa_compact_keep_pair(const uint8_t *keep_q, const uint8_t *keep_k, int S, 
  * larger ones saturate at 65504.
  * scale: every element is multiplied by `scale` in fp32 and the product is then
  * converted to out_dtype.  scale == 1 with out_dtype == dtype is a bit-exact copy; bf16 -> bf16
- * with another scale is SCFA_EUNSUPPORTED.  The attention entry points expect the
- * QUERIES gathered with scale = scfa_q_scale(sm_scale) = sm_scale * log2(e) (their
- * score contraction then yields base-2 exponents directly, see b.); keys, values
- * and everything else are gathered with scale 1.
+ * with another scale is SCFA_EUNSUPPORTED.  The attention entry points expect
+ * queries, keys and values gathered with scale 1 (the inputs' own values).
  */
-float scfa_q_scale(float sm_scale);
 int scfa_gather_rows(const void *x, const int32_t *idx, const int32_t *count,
                      int S, int T, int d, int dtype, int out_dtype, float scale,
                      void *out, void *stream);
 
 /* Q, K and V of one attention call gathered in ONE launch: q_out = q_scale * q[q_idx]
  * (rows < n_q[s]), k_out = k[k_idx], v_out = v[k_idx] (rows < n_k[s]); n_q / n_k
- * nullable (= T).  Same dtype rules as scfa_gather_rows; pass q_scale =
- * scfa_q_scale(sm_scale) for the attention entry points. */
+ * nullable (= T).  Same dtype rules as scfa_gather_rows; pass q_scale = 1 for the
+ * attention entry points. */
 int scfa_gather_qkv(const void *q, const void *k, const void *v,
                     const int32_t *q_idx, const int32_t *k_idx,
                     const int32_t *n_q, const int32_t *n_k,
@@ -252,18 +249,13 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  *
  *   q_perm,k_perm,v_perm  [S,T,d] rows in sorted (hash) or compacted (qkdrop) order, as
  *                         scfa_gather_rows writes them: fp32 for SCFA_F32, fp16
- *                         (out_dtype = SCFA_F16) for SCFA_BF16.  q_perm must have been
- *                         gathered with scale = scfa_q_scale(sm_scale): the kernels
- *                         take <q_perm, k_perm> as the exponent in base 2 and apply no
- *                         scaling of their own (one rounding of q * tau * log2 e to the
- *                         compute format: relative 2^-12 per element for fp16)
+ *                         (out_dtype = SCFA_F16) for SCFA_BF16, all gathered with scale 1
  *   q_sort_key,k_sort_key [S,T] sort keys of those rows (scfa_sort_by_bucket's sort_key_out);
  *                         the QK-dropping entry points take the compacted index vectors
  *                         q_idx, k_idx themselves (one bucket, id 0: position = sort key)
  *   T                     at most SCFA_MAX_T
  *   fwd_work, n_fwd       work list of scfa_block_ranges
- *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d)); the same value
- *                         the queries were gathered with
+ *   sm_scale              tau > 0 (the paper's default is 1/sqrt(d))
  *   o_out                 [B,H,T,d] in ORIGINAL order, dtype of the inputs
  *   lse_out               [B,H,T] float, ORIGINAL order: natural-log logsumexp of the
  *                         scaled scores over allowed keys; -inf for a row with none
@@ -305,7 +297,9 @@ int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
  *                 (dK, dV) are written as zeros
  *   ws, ws_bytes  scratch of at least scfa_attn_bwd_workspace_bytes(S,T,d,dtype),
  *                 256-byte aligned; contents are undefined afterwards
- * q_perm carries tau * log2(e) as in the forward.  dtype: SCFA_BF16 only.  Per query the
+ * q_perm, k_perm, v_perm, sm_scale as in the forward (the kernels multiply their register-
+ * resident operand by tau * log2(e) themselves and round it to fp16: the recomputed scores
+ * carry a relative 2^-12 per element, the forward's logsumexp none).  dtype: SCFA_BF16 only.  Per query the
  * kernels hold LSE * log2(e) and D * (power-of-two dO scale) as sums of three fp16
  * numbers; magnitudes above 60000 are clamped there (|D| <= 2 d max|O| after the
  * scaling of dO, so this needs |O| in the thousands).  dS = P (dP - D) is formed in fp16:

@@ -28,7 +28,7 @@ KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_
 EXPORTS = [
     "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket",
     "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv", "scfa_lsh_buckets",
-    "scfa_compact_keep", "scfa_q_scale", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
+    "scfa_compact_keep", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
     "scfa_attn_bwd_workspace_bytes", "scfa_sort_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
     "scfa_prof_enable", "scfa_prof_reset", "scfa_prof_read", "scfa_prof_occupancy",
@@ -60,8 +60,6 @@ def lib():
         L.scfa_compact_keep_pair.argtypes = [vp, vp, ci, ci, vp, vp, vp, vp, vp, sz, vp]
         L.scfa_gather_qkv.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp, vp, vp]
         L.scfa_gather_rows.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ctypes.c_float, vp, vp]
-        L.scfa_q_scale.argtypes = [ctypes.c_float]
-        L.scfa_q_scale.restype = ctypes.c_float
         L.scfa_block_ranges.argtypes = [ci, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, vp]
         L.scfa_num_work_items.argtypes = [ci, ci, ci]
         ip = ctypes.POINTER(ci)
@@ -81,7 +79,7 @@ def lib():
         L.scfa_prof_occupancy.argtypes = [ci, ci, ip]
         for name in EXPORTS:
             fn = getattr(L, name)
-            if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes", "scfa_sort_workspace_bytes", "scfa_q_scale"):
+            if name not in ("scfa_error_string", "scfa_attn_bwd_workspace_bytes", "scfa_sort_workspace_bytes"):
                 fn.restype = ci
         _lib = L
     return _lib
@@ -222,11 +220,6 @@ def scfa_gather_qkv(q, k, v, q_idx, k_idx, n_q=None, n_k=None, to_f16=False, q_s
                                  dtype_code(q), out_code, float(q_scale), _ptr(out[0]), _ptr(out[1]), _ptr(out[2]),
                                  _stream()), "scfa_gather_qkv")
     return out[0], out[1], out[2]
-
-
-def scfa_q_scale(tau: float) -> float:
-    """The factor the attention kernels expect on the gathered queries: tau * log2(e)."""
-    return float(lib().scfa_q_scale(float(tau)))
 
 
 def scfa_gather_rows(x: torch.Tensor, idx: torch.Tensor, count=None, out=None, to_f16=False, scale=1.0):

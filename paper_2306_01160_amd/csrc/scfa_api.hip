@@ -135,7 +135,7 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const uint
     rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, qkdrop ? n_q : nullptr, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
     rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, d,
-                                   flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
+                                   sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
     if (rc != SCFA_OK) return rc;
     return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd,
                                    S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dq, st);
@@ -226,7 +226,6 @@ int scfa_lsh_buckets(const void* x_q, const void* x_k, const float* R, int S, in
                               bucket_k_out, (hipStream_t)stream);
 }
 
-float scfa_q_scale(float tau) { return tau * 1.4426950408889634f; }
 
 int scfa_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T, int d, int dtype,
                      int out_dtype, float scale, void* out, void* stream)

@@ -239,7 +239,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const uint16_t* __restrict__ do_perm, const uint16_t* __restrict__ aux_perm,
     const float* __restrict__ inv_scale,
     const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
-    const int32_t* __restrict__ work, int n_work, int S, int T, int strict,
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
     float* __restrict__ dk, float* __restrict__ dv)
 {
     constexpr int BM = BWD_TILE_M;
@@ -278,7 +278,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         const uint16_t* vp = v + (seg + k_begin + kr) * D + h * 8;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-            kf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(kp + kk * 16));
+            kf[kk] = scale_f16x8(as_f16x8(*reinterpret_cast<const uint4*>(kp + kk * 16)), tau * LOG2E);   // Q K'^T: base-2 scores
             vf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(vp + kk * 16));
         }
 #pragma unroll
@@ -415,7 +415,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 
     if (kvalid) {
         const float us = inv_scale[s];
-        const float sk = LN2 * us;   // Q' = tau log2(e) Q: dK = tau dS^T Q = ln 2 dS^T Q'
+        const float sk = tau * us;   // dK = tau dS^T Q
         float* dkp = dk + (seg + kpos) * D + 4 * h;
         float* dvp = dv + (seg + kpos) * D + 4 * h;
 #pragma unroll
@@ -434,7 +434,7 @@ template <int D>
 static int launch_dkdv_t(const void* q, const void* k, const void* v, const void* do_perm,
                          const void* aux_perm, const float* inv_scale,
                          const uint32_t* q_key, const uint32_t* k_key, const int32_t* work, int n_work, int S,
-                         int T, int strict, float* dk, float* dv, hipStream_t st)
+                         int T, float tau, int strict, float* dk, float* dv, hipStream_t st)
 {
     const size_t smem = (size_t)DkdvRing<D>::NBUF * DkdvRing<D>::BUF_BYTES;
     static bool attr_set = false;
@@ -446,7 +446,7 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_key, k_key,
-                       work, n_work, S, T, strict, dk, dv);
+                       work, n_work, S, T, tau, strict, dk, dv);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -469,13 +469,13 @@ int occupancy_attn_bwd_dkdv_bf16(int d, int* out)
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
                               const uint32_t* q_key, const uint32_t* k_key, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, int strict, float* dk, float* dv, hipStream_t st)
+                              int S, int T, int d, float tau, int strict, float* dk, float* dv, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DKDV, st);
     if (d == 64)
-        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, strict, dk, dv, st);
+        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, tau, strict, dk, dv, st);
     if (d == 128)
-        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, strict, dk, dv, st);
+        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, tau, strict, dk, dv, st);
     return SCFA_EUNSUPPORTED;
 }
 
@@ -541,7 +541,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         const uint16_t* gp = do_perm + (seg + q_begin + qr) * D + h * 8;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-            qf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16));
+            qf[kk] = scale_f16x8(as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16)), tau * LOG2E);   // K Q'^T: base-2 scores
             gf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(gp + kk * 16));
         }
 #pragma unroll

@@ -72,7 +72,7 @@ __global__ __launch_bounds__(F32_TILE_M) void attn_fwd_f32_kernel(
             float sc = 0.f;
 #pragma unroll
             for (int c = 0; c < D; ++c) sc = fmaf(qr[c], Ks[j][c], sc);
-            sc *= 0.6931471805599453f;   // the queries carry tau * log2(e): back to natural-log units
+            sc *= tau;
             const float m_new = fmaxf(m, sc);
             const float alpha = expf(m - m_new);   // m = -inf on the first taken key -> 0
             const float p = expf(sc - m_new);

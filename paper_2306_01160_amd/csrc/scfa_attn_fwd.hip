@@ -20,21 +20,27 @@
 // NBUF swizzled buffers; one workgroup barrier per tile both publishes the tile that has
 // landed and retires the buffer that is refilled next.
 //
-// The permuted queries arrive multiplied by tau * log2(e), so the contraction yields the
-// scores in base-2 units, x = tau * log2(e) * <q, k>, and no scaling is left per element.
+// The permuted queries and keys are the inputs' own values (bf16 -> fp16 is exact), so the
+// contraction yields <q, k> exactly up to the fp32 accumulation, and the softmax scale enters
+// as one fused multiply-add per element, p = 2^(tau log2(e) (<q, k> - m) + bias): the
+// logsumexp this kernel hands out carries no rounding of the operands.  (The backward kernels
+// fold the scale into their register-resident operand instead and save that instruction: a
+// 2^-12 relative error per element of the recomputed scores does not matter to the gradients,
+// but it would be the largest term of the logsumexp error.)
 //
 // Online softmax (paper App. B.1, running maximum and sum, NaN-safe for fully masked
 // rows): the accumulator is un-normalised and divided by the sum once at the end.  The
-// reference maximum m is only raised when some row's tile maximum exceeds it by more
-// than LAZY_LOG2 (then the accumulator and the sum are rescaled by 2^(m_old - m_new));
-// between raises P = 2^(x - m) may exceed 1 but stays inside the fp16 range.  Once every
+// reference maximum m (of the raw sums) is only raised when some row's tile maximum exceeds
+// it by more than LAZY_LOG2 base-2 units (then the accumulator and the sum are rescaled by
+// 2^(c (m_old - m_new)), c = tau log2(e)); between raises P = 2^(c (s - m)) may exceed 1 but
+// stays inside the fp16 range.  Once every
 // row of a wavefront has a finite reference, the tile maximum is not even computed: the
 // row sum of the packed probabilities, needed anyway, exceeds 2^15 in some lane whenever
 // a probability has left the fp16 range (packing truncates to at most 65504), and only
 // then is the tile redone with its maximum as the new reference.  Because
 // m changes rarely, -m is kept splatted over an accumulator block and the score
-// contraction starts from it: the matrix core delivers x - m and the only per-element
-// vector work left is the exponential, the packing and the row sum.  A row that never
+// contraction starts from it: the matrix core delivers s - m and the only per-element
+// vector work left is the scaling, the exponential, the packing and the row sum.  A row that never
 // sees an allowed key keeps m = -inf and l = 0; its exponent base is 0 (the paper's
 // replacement of -inf by 0), every p is 2^(-inf) = 0, and it is written as zeros with
 // LSE = -inf.
@@ -64,7 +70,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
     uint16_t* __restrict__ o, float* __restrict__ lse, uint16_t* __restrict__ o_f16)
 {
     static_assert(NW * QB * 32 == FWD_TILE_M, "workgroup must cover the forward query tile");
-    (void)tau;   // already folded into the permuted queries
+    const float cexp = tau * LOG2E;   // scores are raw <q, k> sums; the exponent of every probability is cexp * (sum - m)
     constexpr int BN = FWD_TILE_N;
     constexpr int THREADS = NW * 64;
     constexpr int NBUF = FwdRing<D>::NBUF;            // LDS ring; NBUF - 1 tiles are in flight
@@ -117,14 +123,14 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         for (int kk = 0; kk < D / 16; ++kk) touch(qf[b][kk]);   // loaded before the tile loop starts
 
     f32x16 oacc[QB][D / 32];
-    f32x16 start[QB];                // RTZ_BIAS_LOG2 - (finite reference maximum), in all 16 registers
-    float m[QB], thr[QB], lsum[QB];  // reference maximum (base-2 units), raise threshold on x - m, partial row sum
+    f32x16 start[QB];                // -(finite reference maximum), in all 16 registers
+    float m[QB], thr[QB], lsum[QB];  // reference maximum (raw <q, k> units), raise threshold on s - m, partial row sum
 #pragma unroll
     for (int b = 0; b < QB; ++b) {
 #pragma unroll
         for (int db = 0; db < D / 32; ++db) oacc[b][db] = zero16();
 #pragma unroll
-        for (int i = 0; i < 16; ++i) start[b][i] = RTZ_BIAS_LOG2;
+        for (int i = 0; i < 16; ++i) start[b][i] = 0.f;
         m[b] = -INFINITY; thr[b] = -INFINITY; lsum[b] = 0.f;   // the first finite score always raises
     }
 
@@ -228,14 +234,14 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                 const float st_old = start[b][0];
                 const float m_new = fmaxf(m[b], half_max(mx[b]) - st_old);   // tile maximum back in score units
                 const float m_use = m_new == -INFINITY ? 0.f : m_new;
-                float alpha = fast_exp2(m[b] - m_use);                       // m = -inf -> 0
+                float alpha = fast_exp2((m[b] - m_use) * cexp);                       // m = -inf -> 0
                 asm volatile("" : "+v"(alpha));   // rare path: keeps the rescale from being speculated
                 lsum[b] *= alpha;
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db)
 #pragma unroll
                     for (int i = 0; i < 16; ++i) oacc[b][db][i] *= alpha;
-                const float st_new = RTZ_BIAS_LOG2 - m_use;
+                const float st_new = -m_use;
                 const float shift = st_new - st_old;    // scores of this tile move to the new reference
 #pragma unroll
                 for (int kb = 0; kb < 2; ++kb)
@@ -244,12 +250,12 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
 #pragma unroll
                 for (int i = 0; i < 16; ++i) start[b][i] = st_new;
                 m[b] = m_new;
-                thr[b] = m_new == -INFINITY ? -INFINITY : LAZY_LOG2;
+                thr[b] = m_new == -INFINITY ? -INFINITY : LAZY_LOG2 / cexp;
             }
         }
         };
 
-        // P = 2^(x - m), packed to fp16 (truncating: at most 65504, never inf); row sums from the
+        // P = 2^(c (s - m) + bias), packed to fp16 (truncating: at most 65504, never inf); row sums from the
         // packed values
         f16x8 pf[QB][4];
         float lt[QB];
@@ -264,8 +270,8 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                     uint32_t wv[4];
 #pragma unroll
                     for (int j = 0; j < 4; ++j) {
-                        const float p0 = fast_exp2(sacc[kb][b][8 * cc + 2 * j]);
-                        const float p1 = fast_exp2(sacc[kb][b][8 * cc + 2 * j + 1]);
+                        const float p0 = fast_exp2(fmaf(sacc[kb][b][8 * cc + 2 * j], cexp, RTZ_BIAS_LOG2));
+                        const float p1 = fast_exp2(fmaf(sacc[kb][b][8 * cc + 2 * j + 1], cexp, RTZ_BIAS_LOG2));
                         wv[j] = pack_f16(p0, p1);
                     }
                     l0 = add_pair(wv[0], l0); l1 = add_pair(wv[1], l1);
@@ -366,7 +372,7 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
                         *reinterpret_cast<uint2*>(o_f16 + row + db * 32 + 8 * g) = hk;
                     }
                 }
-            if (h == 0) lse[seg + qpos[b]] = ltot > 0.f ? (m[b] + log2f(ltot)) * LN2 : -INFINITY;
+            if (h == 0) lse[seg + qpos[b]] = ltot > 0.f ? (m[b] * cexp + log2f(ltot)) * LN2 : -INFINITY;
         }
     }
 }

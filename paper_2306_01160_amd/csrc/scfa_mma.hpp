@@ -46,6 +46,15 @@ __device__ __forceinline__ uint32_t pack_f16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
+// every element of a fragment times c, in fp32, rounded to fp16 (nearest even)
+__device__ __forceinline__ f16x8 scale_f16x8(f16x8 v, float c)
+{
+    f16x8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (_Float16)((float)v[e] * c);
+    return r;
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // Added to the exponent of every probability that is then truncated to

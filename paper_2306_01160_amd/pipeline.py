@@ -62,8 +62,7 @@ def hash_forward(q, k, v, bucket_q, bucket_k, nb, sm_scale, need_bwd=True, stric
     flags = sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0
     (q_idx, q_bs, q_off, q_key), (k_idx, k_bs, k_off, k_key) = sc.scfa_sort_by_bucket_pair(
         _seg(bucket_q), _seg(bucket_k), nb, want_sorted=False)
-    q_p, k_p, v_p = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, to_f16=q.dtype == torch.bfloat16,
-                                       q_scale=sc.scfa_q_scale(sm_scale))
+    q_p, k_p, v_p = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, to_f16=q.dtype == torch.bfloat16)
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_HASH, q_idx, k_idx, q_off, k_off, nb, tiles,
                                                         want_bwd=need_bwd, flags=flags)
     o_f16 = _o_f16_buffer(q, need_bwd)
@@ -86,7 +85,7 @@ def qkdrop_forward(q, k, v, keep_q, keep_k, sm_scale, need_bwd=True, strict=Fals
     flags = sc.SCFA_FLAG_STRICT_CAUSAL if strict else 0
     (q_idx, n_q), (k_idx, n_k) = sc.scfa_compact_keep_pair(_seg(keep_q), _seg(keep_k))
     q_c, k_c, v_c = sc.scfa_gather_qkv(_seg(q), _seg(k), _seg(v), q_idx, k_idx, n_q, n_k,
-                                       to_f16=q.dtype == torch.bfloat16, q_scale=sc.scfa_q_scale(sm_scale))
+                                       to_f16=q.dtype == torch.bfloat16)
     fwd_work, bwd_work, counters = sc.scfa_block_ranges(sc.SCFA_QKDROP, q_idx, k_idx, n_q, n_k, 1, tiles,
                                                         want_bwd=need_bwd, flags=flags)
     o_f16 = _o_f16_buffer(q, need_bwd)

@@ -107,14 +107,13 @@ def test_gather_rows_bf16_to_f16_compute_format():
 
 
 def test_gather_rows_scaled_queries():
-    """The query gather multiplies by tau * log2(e) before the rounding to the compute format
-    (fp32 product, then one conversion): equals torch's float multiply + conversion bit for bit."""
+    """A gather with a scale multiplies in fp32 before the one rounding to the output format:
+    equals torch's float multiply + conversion bit for bit."""
     S, T, d = 2, 515, 64
     rng = np.random.default_rng(11)
     x = rng.standard_normal((S, T, d)).astype(np.float32)
     idx = np.stack([rng.permutation(T) for _ in range(S)]).astype(np.int32)
-    scale = sc.scfa_q_scale(0.125)
-    assert scale == float(np.float32(0.125) * np.float32(1.4426950408889634))
+    scale = float(np.float32(0.125) * np.float32(1.4426950408889634))
     xb = torch.from_numpy(x).to(DEV).to(torch.bfloat16)
     g = torch.gather(xb, 1, _t(idx).long()[..., None].expand(-1, -1, d)).float()
     out = sc.scfa_gather_rows(xb, _t(idx), to_f16=True, scale=scale)
@@ -149,7 +148,7 @@ def test_pair_entry_points_match_single_calls(S, T, nb):
     d = 64
     q, k, v = (torch.from_numpy(rng.standard_normal((S, T, d)).astype(np.float32)).to(DEV).to(torch.bfloat16)
                for _ in range(3))
-    scale = sc.scfa_q_scale(0.125)
+    scale = float(np.float32(0.125) * np.float32(1.4426950408889634))
     for nq_, nk_ in ((None, None), (cnq, cnk)):
         i_q, i_k = (qi, ki) if nq_ is None else (cqi, cki)
         sent = [torch.full((S, T, d), 3.0, dtype=torch.float16, device=DEV) for _ in range(3)]
