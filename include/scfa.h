@@ -13,7 +13,7 @@
  *   scfa_lsh_buckets                          (optional) bucket ids from the rows, Sec. 4.2
  *   scfa_sort_by_bucket[_pair] / scfa_compact_keep[_pair]
  *                                             stable permutation: original-index vectors, sort keys
- *   scfa_gather_qkv / scfa_gather_rows        permuted / compacted Q (pre-scaled), K, V
+ *   scfa_gather_qkv / scfa_gather_rows        permuted / compacted Q, K, V
  *   scfa_block_ranges                         tile-skip schedule (work lists)
  *   scfa_hash_attn_fwd / scfa_qkdrop_attn_fwd O and logsumexp, written in ORIGINAL order
  *   scfa_hash_attn_bwd / scfa_qkdrop_attn_bwd dQ, dK, dV, written in ORIGINAL order

@@ -17,8 +17,10 @@
 // magnitude lies in [1, 2) before it is converted to fp16; the gradients are multiplied
 // by the inverse power at the end.  Both scalings are exact.
 //
-// The permuted queries arrive multiplied by tau * log2(e) (the forward's convention), so
-// Q K^T is the score in base-2 units and dK = ln 2 * dS^T Q'.  The per-row subtractions of
+// The operand a workgroup keeps in registers (its queries Q' in the dQ kernel, its keys K' in the
+// dK/dV kernel) is multiplied by tau * log2(e) once per work item and rounded to fp16, so the
+// score contraction is in base-2 units; the other operand streams through LDS as it is, so
+// dK = tau * dS^T Q and dQ = tau * dS K need no correction.  The per-row subtractions of
 // P = 2^(x - LSE log2 e) and dS = P (dP - D) are folded into the contractions:
 //   - where the row is a lane (dQ kernel) the accumulators start from -LSE log2 e and -D;
 //   - where the row is a register (dK/dV kernel) one more contraction step of 16 slots is
@@ -216,7 +218,7 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
 // ===========================================================================
 // dK / dV: a workgroup owns 128 keys of one bucket (32 per wavefront, in the lanes)
 // and walks the 64-row query tiles that can see them.  Per tile:
-//   X = Q' K^T - LSE log2 e, dP' = dO V^T - D (queries x keys; lane = key, registers =
+//   X = Q K'^T - LSE log2 e, dP' = dO V^T - D (queries x keys; lane = key, registers =
 //   queries; the subtractions ride in a 16-slot contraction step on the aux rows)
 //   P = 2^X, dS = P dP'
 //   dV^T += dO^T P,  dK^T += Q^T dS   (d x keys; Q^T, dO^T by transposing LDS reads)
