@@ -153,6 +153,30 @@ def test_seeded_random_shapes(seed):
     _full_check(wl)
 
 
+@pytest.mark.parametrize("seed", range(2000, 2024))
+def test_seeded_random_shapes_many_buckets(seed):
+    """As above with up to 256 buckets (rows that see one or two keys: the logsumexp is then a single
+    score), bucket sizes skewed like 1 / rank, and keep rates down to 2 %."""
+    rng = np.random.default_rng(seed)
+    T = int(rng.integers(1, 3000))
+    d = int(rng.choice([64, 128]))
+    B, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    strict = bool(rng.integers(0, 2))
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        wl = W.hash_uniform(seed, B, H, T, d, int(rng.integers(1, 257)))
+    elif kind == 1:
+        nb = int(rng.integers(2, 129))
+        wl = W.hash_uniform(seed, B, H, T, d, nb)
+        p = 1.0 / np.arange(1, nb + 1); p /= p.sum()
+        wl.lab_q[...] = rng.choice(nb, size=wl.lab_q.shape, p=p).astype(np.int32)
+        wl.lab_k[...] = rng.choice(nb, size=wl.lab_k.shape, p=p).astype(np.int32)
+    else:
+        wl = W.qkdrop_bernoulli(seed, B, H, T, d, float(rng.uniform(0.02, 1.0)), float(rng.uniform(0.02, 1.0)))
+    wl.meta["strict"] = strict
+    _full_check(wl)
+
+
 # --------------------------------------------------------------- degenerate cases
 
 def test_bucket_present_in_q_but_absent_in_k_gives_zero_rows():
