@@ -439,12 +439,8 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
                          int T, float tau, int strict, float* dk, float* dv, hipStream_t st)
 {
     const size_t smem = (size_t)DkdvRing<D>::NBUF * DkdvRing<D>::BUF_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dkdv_f16_kernel<D>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed{0};
+    { const int rc_ = allow_dynamic_lds(reinterpret_cast<const void*>(&attn_bwd_dkdv_f16_kernel<D>), (int)smem, lds_allowed); if (rc_ != SCFA_OK) return rc_; }
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_key, k_key,
@@ -695,12 +691,8 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
                        float tau, int strict, float* dq, hipStream_t st)
 {
     const size_t smem = (size_t)DqRing<D>::NBUF * DqRing<D>::BUF_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_bwd_dq_f16_kernel<D>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed{0};
+    { const int rc_ = allow_dynamic_lds(reinterpret_cast<const void*>(&attn_bwd_dq_f16_kernel<D>), (int)smem, lds_allowed); if (rc_ != SCFA_OK) return rc_; }
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dq_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key,

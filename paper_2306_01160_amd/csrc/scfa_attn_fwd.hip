@@ -383,12 +383,8 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const uint3
                         float* lse, void* o_f16, hipStream_t st)
 {
     constexpr size_t smem = (size_t)FwdRing<D>::NBUF * FwdRing<D>::BUF_BYTES;
-    static bool attr_set = false;
-    if (!attr_set) {
-        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_f16_kernel<D, NW, QB>),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed{0};
+    { const int rc_ = allow_dynamic_lds(reinterpret_cast<const void*>(&attn_fwd_f16_kernel<D, NW, QB>), (int)smem, lds_allowed); if (rc_ != SCFA_OK) return rc_; }
     dim3 grid((unsigned)((size_t)S * n_work));
     hipLaunchKernelGGL((attn_fwd_f16_kernel<D, NW, QB>), grid, dim3(NW * 64), smem, st, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, q_key, k_key, work, n_work, S, T, tau,

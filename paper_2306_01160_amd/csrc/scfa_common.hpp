@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 #include "scfa.h"
 
@@ -22,6 +23,20 @@ inline int hip_fail(hipError_t e)
         hipError_t _e = (expr);                            \
         if (_e != hipSuccess) return ::scfa::hip_fail(_e); \
     } while (0)
+
+// A kernel that takes more than 64 KB of dynamic LDS has to be told so once on every device it
+// runs on.  `done` (one per kernel instantiation) remembers the devices already prepared, one
+// bit each; the current device is the one the caller's stream belongs to.
+inline int allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done)
+{
+    int dev = 0;
+    SCFA_HIP_TRY(hipGetDevice(&dev));
+    const unsigned long long bit = 1ull << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return SCFA_OK;
+    SCFA_HIP_TRY(hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes));
+    done.fetch_or(bit, std::memory_order_release);
+    return SCFA_OK;
+}
 
 // ---- profiling hooks (scfa_prof_*) -----------------------------------------
 struct ProfScope {

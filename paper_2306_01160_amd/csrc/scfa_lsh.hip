@@ -123,12 +123,10 @@ int launch_lsh_buckets(int n_problems, const void* x0, const void* x1, const flo
     ProfScope prof(SCFA_K_LSH, st);
 #define SCFA_LSH_LAUNCH(DD, BB)                                                                              \
     do {                                                                                                     \
-        static bool attr_set = false;                                                                        \
-        if (!attr_set) {                                                                                     \
-            SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&lsh_buckets_kernel<DD, BB>),     \
-                                             hipFuncAttributeMaxDynamicSharedMemorySize, 64 * 1024));        \
-            attr_set = true;                                                                                 \
-        }                                                                                                    \
+        static std::atomic<unsigned long long> lds_allowed{0}; \
+        const int rc_ = allow_dynamic_lds(reinterpret_cast<const void*>(&lsh_buckets_kernel<DD, BB>), 64 * 1024, \
+                                          lds_allowed); \
+        if (rc_ != SCFA_OK) return rc_; \
         hipLaunchKernelGGL((lsh_buckets_kernel<DD, BB>), grid, block, smem, st, p0, p1, R, H, T, r);         \
     } while (0)
     if (d == 64 && bf16) SCFA_LSH_LAUNCH(64, true);

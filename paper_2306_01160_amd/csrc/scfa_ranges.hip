@@ -328,12 +328,8 @@ int launch_block_ranges(int variant, const int32_t* q_idx, const int32_t* k_idx,
     int shift = 0;            // the searched vector is staged in LDS whole, or every 2^shift-th entry of it
     while (small + sizeof(int32_t) * ((((size_t)T - 1) >> shift) + 1) > 144 * 1024) ++shift;
     const size_t smem = small + sizeof(int32_t) * ((((size_t)T - 1) >> shift) + 1);
-    static bool attr_set = false;
-    if (!attr_set) {
-        SCFA_HIP_TRY(hipFuncSetAttribute(reinterpret_cast<const void*>(&block_ranges_kernel),
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 144 * 1024));
-        attr_set = true;
-    }
+    static std::atomic<unsigned long long> lds_allowed{0};
+    { const int rc_ = allow_dynamic_lds(reinterpret_cast<const void*>(&block_ranges_kernel), 144 * 1024, lds_allowed); if (rc_ != SCFA_OK) return rc_; }
     ProfScope prof(SCFA_K_RANGES, st);
     hipLaunchKernelGGL(block_ranges_kernel, dim3(S, bwd_work ? 2 : 1), dim3(RANGES_THREADS), smem, st, variant, q_idx,
                        k_idx, q_off, k_off, T, nb, fwd_m, fwd_n, bwd_n, bwd_m, n_fwd, n_bwd, shift, strict, fwd_work,
