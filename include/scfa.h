@@ -105,6 +105,25 @@ int scfa_sort_by_bucket(const int32_t *bucket, int S, int T, int nb,
                         int32_t *bucket_off_out, uint32_t *sort_key_out,
                         void *ws, size_t ws_bytes, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): scfa_sort_by_bucket with the chunk
+ * counters of the multi-workgroup sort in a device array the library itself owns, instead
+ * of a caller workspace.  Arguments and outputs as scfa_sort_by_bucket (same bits).  The
+ * call allocates and frees nothing and creates no events (the scfa_prof_* timers skip it);
+ * its first call on a device looks the array's address up once, with that device current.
+ * `stream` must belong to the current device (SCFA_EINVAL otherwise).
+ * Limit: scfa_sort_workspace_bytes-worth of counters, 4 * S * chunks * nb bytes (chunks =
+ * min(ceil(256 / S), T / 4096, 64) for T >= 8192, else none), must not exceed
+ * SCFA_STATIC_SCRATCH_BYTES; larger problems return SCFA_EWORKSPACE and launch nothing.
+ * Every device the library runs on holds the array until the process ends.  All calls on
+ * one device share it: calls that may overlap on one device (different streams, or threads)
+ * race on the counters and must be serialised by the caller. */
+#define SCFA_STATIC_SCRATCH_BYTES (256 * 1024)
+int scfa_sort_by_bucket_static(const int32_t *bucket, int S, int T, int nb,
+                               int32_t *idx_out, int32_t *bucket_sorted_out,
+                               int32_t *bucket_off_out, uint32_t *sort_key_out,
+                               void *stream);
+
 /* The same sort for the query and the key bucket ids of one attention call in ONE
  * launch (Sec. 3.2 sorts both); outputs as above, one set per side.  The *_sorted_out
  * and *_sort_key_out pointers are nullable. */

@@ -26,7 +26,7 @@ KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_
               "bwd_dkdv": 6, "bwd_dq": 7, "fill": 8, "lsh": 9}
 
 EXPORTS = [
-    "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket",
+    "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket", "scfa_sort_by_bucket_static",
     "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv", "scfa_lsh_buckets",
     "scfa_compact_keep", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
@@ -54,6 +54,7 @@ def lib():
         L.scfa_error_string.restype = ctypes.c_char_p
         L.scfa_error_string.argtypes = [ci]
         L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
+        L.scfa_sort_by_bucket_static.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp, sz, vp]
         L.scfa_lsh_buckets.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
         L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -166,6 +167,13 @@ def scfa_sort_by_bucket(bucket: torch.Tensor, nb: int, want_sort_key=False, use_
     _check(lib().scfa_sort_by_bucket(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _ptr(key),
                                      _ptr(ws), ws_bytes, _stream()), "scfa_sort_by_bucket")
     return (idx, bsorted, off, key) if want_sort_key else (idx, bsorted, off)
+
+
+def scfa_sort_by_bucket_static(bucket: torch.Tensor, nb: int, idx: torch.Tensor, bsorted, off: torch.Tensor, key):
+    """The sort with the library's own scratch: outputs are passed in (the call allocates nothing)."""
+    S, T = bucket.shape
+    _check(lib().scfa_sort_by_bucket_static(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _ptr(key),
+                                            _stream()), "scfa_sort_by_bucket_static")
 
 
 def scfa_compact_keep(keep: torch.Tensor, use_ws=True):

@@ -35,7 +35,7 @@ hipEvent_t prof_get_event()
 
 ProfScope::ProfScope(int kernel_id, hipStream_t s) : kid(kernel_id), stream(s), slot(-1)
 {
-    if (!g_prof_on) return;
+    if (!g_prof_on || kernel_id < 0) return;   // a negative id: a launch that must not create events
     std::lock_guard<std::mutex> lk(g_prof_mu);
     if (g_prof_recs.size() >= PROF_MAX_RECS) return;
     ProfRec r{kernel_id, prof_get_event(), prof_get_event()};
@@ -179,6 +179,17 @@ int scfa_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* id
     if (sort_key_out && T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;
     return launch_sort_by_bucket(1, bucket, nullptr, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, sort_key_out,
                                  nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, (hipStream_t)stream);
+}
+
+int scfa_sort_by_bucket_static(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
+                               int32_t* bucket_sorted_out, int32_t* bucket_off_out, uint32_t* sort_key_out,
+                               void* stream)
+{
+    if (!bucket || !idx_out || !bucket_off_out || S <= 0 || T <= 0 || nb <= 0) return SCFA_EINVAL;
+    if (nb > SCFA_MAX_BUCKETS) return SCFA_EUNSUPPORTED;
+    if (sort_key_out && T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;
+    return launch_sort_by_bucket_static(bucket, S, T, nb, idx_out, bucket_sorted_out, bucket_off_out, sort_key_out,
+                                        (hipStream_t)stream);
 }
 
 int scfa_sort_by_bucket_pair(const int32_t* bucket_q, const int32_t* bucket_k, int S, int T, int nb,

@@ -220,14 +220,14 @@ size_t sort_workspace_bytes(int n_problems, int S, int T, int nb)
 
 template <bool KEEP_MODE>
 static int launch_sort_t(int kid, int n_problems, const SortProblem& p0, const SortProblem& p1, int S, int T, int nb,
-                         int nbits, void* ws, size_t ws_bytes, hipStream_t st)
+                         int nbits, void* ws, size_t ws_bytes, hipStream_t st, bool timed = true)
 {
     const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + 2 * (size_t)nb + 1);
     int n_chunks = sort_chunks(S * n_problems, T);
     if (!ws || ws_bytes < sort_workspace_bytes(n_problems, S, T, nb)) n_chunks = 1;   // no scratch: one workgroup per segment
     int chunk_len = sort_chunk_len(T, n_chunks);
     n_chunks = (T + chunk_len - 1) / chunk_len;      // rounding the length up may leave fewer chunks
-    ProfScope prof(kid, st);
+    ProfScope prof(timed ? kid : -1, st);            // the timers create events: not on the allocation-free path
     if (n_chunks > 1)
         hipLaunchKernelGGL(sort_chunk_count_kernel<KEEP_MODE>, dim3(S * n_problems * n_chunks), dim3(COUNT_THREADS),
                            sizeof(int32_t) * nb, st, p0.keys, p1.keys, S, T, nb, n_chunks, chunk_len, (int32_t*)ws);
@@ -245,6 +245,54 @@ int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t*
     while ((1 << nbits) < nb) ++nbits;
     const SortProblem p0{bucket0, idx0, sorted0, off0, key0}, p1{bucket1, idx1, sorted1, off1, key1};
     return launch_sort_t<false>(SCFA_K_SORT, n_problems, p0, p1, S, T, nb, nbits, ws, ws_bytes, st);
+}
+
+// ---------------------------------------------------------------------------
+// The sort with the chunk counters in memory the library owns: a file-scope device array instead
+// of a caller workspace, for callers that cannot allocate.  Every device holds its own copy of the
+// array at its own address; the address is looked up once per device (with that device current)
+// and kept.  In host code the array's name is only a handle for that lookup, never an address.
+static __device__ __align__(256) unsigned char scratch[SCFA_STATIC_SCRATCH_BYTES];
+
+constexpr int MAX_DEVICES = 64;
+static std::atomic<void*> g_scratch_ptr[MAX_DEVICES];
+
+// device address of `scratch` on the device `st` belongs to, which must be the current device
+static int static_scratch(hipStream_t st, void** out)
+{
+    int dev = 0;
+    SCFA_HIP_TRY(hipGetDevice(&dev));
+    if (st) {
+        int sdev = -1;
+        SCFA_HIP_TRY(hipStreamGetDevice(st, &sdev));
+        if (sdev != dev) return SCFA_EINVAL;
+    }
+    if (dev < 0 || dev >= MAX_DEVICES) return SCFA_EUNSUPPORTED;
+    void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        SCFA_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return SCFA_EHIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *out = p;
+    return SCFA_OK;
+}
+
+int launch_sort_by_bucket_static(const int32_t* bucket, int S, int T, int nb, int32_t* idx, int32_t* sorted,
+                                 int32_t* off, uint32_t* key, hipStream_t st)
+{
+    // the chunk counters must fit the array: nothing is launched otherwise
+    const size_t need = sort_workspace_bytes(1, S, T, nb);
+    if (need > SCFA_STATIC_SCRATCH_BYTES) return SCFA_EWORKSPACE;
+    void* ptr = nullptr;
+    const int rc = static_scratch(st, &ptr);
+    if (rc != SCFA_OK) return rc;
+    int nbits = 0;
+    while ((1 << nbits) < nb) ++nbits;
+    const SortProblem p0{bucket, idx, sorted, off, key}, p1{nullptr, nullptr, nullptr, nullptr, nullptr};
+    // every counter the sort kernel reads is written by the counting kernel of the same call, so
+    // what an earlier call left in the array does not matter
+    return launch_sort_t<false>(SCFA_K_SORT, 1, p0, p1, S, T, nb, nbits, ptr, SCFA_STATIC_SCRATCH_BYTES, st, false);
 }
 
 int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,
