@@ -349,13 +349,41 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
             sacc[qb] = mfma16(ax, sub_lse, zero16());
             pacc[qb] = mfma16(ax, sub_delta, zero16());
         }
-#pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
+        if (D == 128) {
+            // one wavefront per SIMD: nobody else hides its LDS latency, so the row fragments of a contraction
+            // step are requested a full step (four matrix instructions) before they are used
+            f16x8 fq[2][2], fg[2][2];
 #pragma unroll
             for (int qb = 0; qb < 2; ++qb) {
-                sacc[qb] = mfma16(swz_rows<D>(Qt, qb * 32 + l32, kk * 16 + h * 8), kf[kk], sacc[qb]);
-                pacc[qb] = mfma16(swz_rows<D>(Gt, qb * 32 + l32, kk * 16 + h * 8), vf[kk], pacc[qb]);
+                fq[0][qb] = swz_rows<D>(Qt, qb * 32 + l32, h * 8);
+                fg[0][qb] = swz_rows<D>(Gt, qb * 32 + l32, h * 8);
             }
+#pragma unroll
+            for (int kk = 0; kk < D / 16; ++kk) {
+                if (kk + 1 < D / 16) {
+#pragma unroll
+                    for (int qb = 0; qb < 2; ++qb) {
+                        fq[(kk + 1) & 1][qb] = swz_rows<D>(Qt, qb * 32 + l32, (kk + 1) * 16 + h * 8);
+                        fg[(kk + 1) & 1][qb] = swz_rows<D>(Gt, qb * 32 + l32, (kk + 1) * 16 + h * 8);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    sacc[qb] = mfma16(fq[kk & 1][qb], kf[kk], sacc[qb]);
+                    pacc[qb] = mfma16(fg[kk & 1][qb], vf[kk], pacc[qb]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+                for (int qb = 0; qb < 2; ++qb) {
+                    sacc[qb] = mfma16(swz_rows<D>(Qt, qb * 32 + l32, kk * 16 + h * 8), kf[kk], sacc[qb]);
+                    pacc[qb] = mfma16(swz_rows<D>(Gt, qb * 32 + l32, kk * 16 + h * 8), vf[kk], pacc[qb]);
+                }
+        }
 
 #pragma unroll
         for (int qb = 0; qb < 2; ++qb)
@@ -382,8 +410,13 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
             for (int db = 0; db < D / 32; ++db) {
                 int oa, ob;
                 swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
-                dvacc[db] = mfma16(swz_trans(Gt, oa, ob), pf, dvacc[db]);
-                dkacc[db] = mfma16(swz_trans(Qt, oa, ob), sf, dkacc[db]);
+                if (D == 128) {   // 128 accumulator registers: kept out of the architectural VGPRs
+                    acc_mfma16(dvacc[db], swz_trans(Gt, oa, ob), pf);
+                    acc_mfma16(dkacc[db], swz_trans(Qt, oa, ob), sf);
+                } else {
+                    dvacc[db] = mfma16(swz_trans(Gt, oa, ob), pf, dvacc[db]);
+                    dkacc[db] = mfma16(swz_trans(Qt, oa, ob), sf, dkacc[db]);
+                }
             }
         }
     };
@@ -414,6 +447,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     for (; jt < n_masked; ++jt) step(jt, std::true_type{});
     for (; jt < n_tiles; ++jt) step(jt, std::false_type{});
     wait_async<0>();   // nothing may still be landing in LDS when the wavefront ends
+    if (D == 128) acc_mfma_drain();
 
     if (kvalid) {
         const float us = inv_scale[s];

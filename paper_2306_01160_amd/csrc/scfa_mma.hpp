@@ -32,6 +32,22 @@ __device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
 }
 
+// The same instruction with the accumulator held in the accumulation registers (AccVGPRs), for
+// accumulators that live across a whole work item and are only read at its end: they then take no
+// architectural VGPRs.  Issued from inline assembly (the compiler would keep a VGPR form); a dependent
+// accumulate into the same registers needs no wait, and whoever reads the accumulator afterwards must
+// let the last instruction retire (acc_mfma_drain) -- the compiler does not know this statement is a
+// matrix instruction.  Not volatile: a pure function of its operands, so LDS reads may be scheduled
+// across it.
+__device__ __forceinline__ void acc_mfma16(f32x16& acc, f16x8 a, f16x8 b)
+{
+    asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+__device__ __forceinline__ void acc_mfma_drain()
+{
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+}
+
 __device__ __forceinline__ f32x16 zero16()
 {
     f32x16 z;
