@@ -61,7 +61,11 @@ extern "C" {
 #define SCFA_FLAG_STRICT_CAUSAL 1   /* allowed keys are at strictly earlier positions */
 
 #define SCFA_MAX_BUCKETS 256
-#define SCFA_MAX_T 16777200     /* positions take the low 24 bits of a sort key */
+#define SCFA_MAX_T 16777200     /* positions take the low 24 bits of a sort key.  Effective limits are lower:
+                                 * scfa_block_ranges needs ceil(T / 128) + nb <= 8192 (T of about one million:
+                                 * its ranking scratch lives in LDS), and the attention entry points need
+                                 * T * d * sizeof(element) < 2^31 (byte offsets inside a segment are 32-bit);
+                                 * both return SCFA_EUNSUPPORTED beyond that. */
 #define SCFA_WORK_STRIDE 8      /* int32 words per work item */
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -76,7 +80,7 @@ const char *scfa_error_string(int code);
 
 /* ------------------------------------------------------------------------
  * a1. Stable sort of token positions by bucket id, per segment (Sec. 3.2:
- * "reorder Q, K, V by sorting them along the sequence length dimension"; the
+ * the rows of Q, K and V are brought into bucket order along the sequence dimension; the
  * sort must be stable so that original positions stay increasing inside a
  * bucket).
  *
@@ -181,9 +185,10 @@ int scfa_compact_keep_pair(const uint8_t *keep_q, const uint8_t *keep_k, int S, 
  * and must not overlap.  dtype: SCFA_BF16 or SCFA_F32; d*sizeof(elem) must be a
  * multiple of 16.
  * out_dtype: equal to dtype, or SCFA_F16 for SCFA_BF16 input: the compute format of
- * the attention kernels.  bf16 -> fp16 rounds to nearest even; it is exact for
+ * the attention kernels.  bf16 -> fp16 rounds to nearest even (IEEE): exact for
  * magnitudes in [2^-17, 65504], smaller ones lose low bits (absolute error < 2^-25),
- * larger ones saturate at 65504.
+ * larger ones become +-inf and NaN stays NaN -- an input outside the compute format then
+ * shows as non-finite attention outputs instead of being replaced by a finite value.
  * scale: every element is multiplied by `scale` in fp32 and the product is then
  * converted to out_dtype.  scale == 1 with out_dtype == dtype is a bit-exact copy; bf16 -> bf16
  * with another scale is SCFA_EUNSUPPORTED.  The attention entry points expect
@@ -282,8 +287,11 @@ int scfa_tile_config(int d, int dtype, int *fwd_tile_m, int *fwd_tile_n,
  *                         (11 significant bits instead of bf16's 8), for the backward's
  *                         D = <dO, O>; pass it to the backward as o_f16.  Rows of dropped
  *                         queries are not written.
- * d: 64 or 128.  SCFA_BF16: scores are bf16 x bf16 products accumulated in fp32; P is
- * rounded to fp16 and V converted to fp16 (exact for |v| in [2^-14, 65504]) for P.V.
+ * d: 64 or 128.  SCFA_BF16: the permuted copies are fp16 (the bf16 values themselves for
+ * magnitudes in [2^-17, 65504]); scores are fp16 x fp16 products on the matrix cores,
+ * exact, accumulated in fp32; the softmax runs in fp32; P is rounded to fp16 for P.V, which
+ * accumulates in fp32.  Finite inputs of any scale inside that range are handled (the
+ * logsumexp is exact to fp32 rounding whatever the size of the logits).
  *
  * scfa_qkdrop_attn_fwd additionally takes the kept-query counts n_q [S] and
  * writes zeros / -inf for the dropped query rows idx[n_q[s] .. T).
@@ -316,14 +324,16 @@ int scfa_qkdrop_attn_fwd(const void *q_c, const void *k_c, const void *v_c,
  *                 (dK, dV) are written as zeros
  *   ws, ws_bytes  scratch of at least scfa_attn_bwd_workspace_bytes(S,T,d,dtype),
  *                 256-byte aligned; contents are undefined afterwards
- * q_perm, k_perm, v_perm, sm_scale as in the forward (the kernels multiply their register-
- * resident operand by tau * log2(e) themselves and round it to fp16: the recomputed scores
- * carry a relative 2^-12 per element, the forward's logsumexp none).  dtype: SCFA_BF16 only.  Per query the
- * kernels hold LSE * log2(e) and D * (power-of-two dO scale) as sums of three fp16
- * numbers; magnitudes above 60000 are clamped there (|D| <= 2 d max|O| after the
- * scaling of dO, so this needs |O| in the thousands).  dS = P (dP - D) is formed in fp16:
- * |<dO_i, V_j> - D_i| (dO scaled to a largest magnitude in [1, 2)) must stay below the
- * fp16 range, 65504, i.e. |V| in the hundreds at the least.
+ * q_perm, k_perm, v_perm, sm_scale as in the forward: the scores are recomputed from the same
+ * exact products and scaled per element in fp32.  dtype: SCFA_BF16 only.
+ * Range of the backward (beyond it the gradients of the rows concerned are NON-FINITE, not
+ * finite and wrong): per query the kernels hold LSE / tau and D * (power-of-two dO scale, largest
+ * |dO| of the segment in [1, 2)) as sums of three fp16 numbers, which reach |LSE| / tau < 2.09e6
+ * (logits of +-2.6e5 at tau = 1/8) and |D| < 65504 (|D| <= 2 d max|O|: |O| in the hundreds);
+ * dS = P (dP - D) is formed in fp16: |<dO_i, V_j> - D_i| must stay below 65504, i.e. |V| in the
+ * hundreds at the least.  A softmax that is one-hot to fp32 precision (logits in the tens of
+ * thousands) has dS = P (dP - D) with dP = D up to rounding: its gradients are cancellation
+ * noise of relative size 2^-11 against |dO| |V| |K| tau, not against their own (vanishing) size.
  *
  * scfa_qkdrop_attn_bwd additionally takes n_q, n_k [S] (kept counts).
  */

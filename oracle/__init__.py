@@ -6,7 +6,7 @@ never imports it.
 
 Floating-point part: ``scfa_oracle.c`` (plain C, fp64), the definition of masked
 causal softmax attention and its derivatives written out on the original,
-unpermuted tensors (paper Sec. 3: the method "implements the exact computation",
+unpermuted tensors (paper Sec. 3: the method computes exact attention under the mask, no approximation,
 so the oracle is that computation's plain definition).
 
 Integer part (this file, numpy): the stable sort by bucket and the compaction
@@ -258,49 +258,40 @@ def allowed_mask(lab_q, lab_k, variant, strict=False):
     return causal & (lab_q[:, None] != 0) & (lab_k[None, :] != 0)
 
 
+def _per_tile(x, B):
+    """Smallest and largest entry of every block of B consecutive entries (the last block may be short)."""
+    x = np.asarray(x)
+    starts = np.arange(0, x.shape[0], B)
+    return np.minimum.reduceat(x, starts), np.maximum.reduceat(x, starts)
+
+
 def paper_tile_ranges_qk(q_idx, k_idx, Bm, Bn):
-    """Key-tile range ``[0, end)`` per query tile, QK-sparse rule of Alg. 1:
-    ``end`` counts the key blocks whose smallest index is <= the largest query
-    index of the block.  ``q_idx`` / ``k_idx`` are the (padded) index vectors of
-    the compacted tensors of ONE segment."""
-    q_idx = np.asarray(q_idx); k_idx = np.asarray(k_idx)
-    out = []
-    for m0 in range(0, q_idx.shape[0], Bm):
-        qb = q_idx[m0:m0 + Bm]
-        end = 0
-        for n0 in range(0, k_idx.shape[0], Bn):
-            kb = k_idx[n0:n0 + Bn]
-            if kb.min() <= qb.max():
-                end += 1
-        out.append((0, end))
-    return out
+    """Key-tile range ``[0, end)`` per query tile under the QK-sparse rule (paper Sec. 3.1, Alg. 1): a key
+    tile is visited iff its earliest key is not later than the query tile's latest query, and ``end`` is
+    the NUMBER of such tiles (the compacted keys are in increasing order, so they form a prefix).
+    ``q_idx`` / ``k_idx`` are the (padded) index vectors of the compacted tensors of ONE segment."""
+    _, q_last = _per_tile(q_idx, Bm)
+    k_first, _ = _per_tile(k_idx, Bn)
+    return [(0, int(np.count_nonzero(k_first <= ql))) for ql in q_last]
 
 
 def paper_tile_ranges_hash(q_idx, k_idx, q_hash, k_hash, Bm, Bn):
-    """Key-tile range ``[start, end)`` per query tile, hash rule of Alg. 2:
-    ``start`` counts key blocks whose largest bucket is below the query block's
-    smallest bucket, ``end_hash`` counts key blocks whose smallest bucket is <=
-    the query block's largest bucket, and ``end`` is refined to one past the
-    last block in ``[start, end_hash)`` whose smallest key index is <= the
-    largest query index (``end_hash`` if there is none, as the listing reads)."""
-    q_idx = np.asarray(q_idx); k_idx = np.asarray(k_idx)
-    q_hash = np.asarray(q_hash); k_hash = np.asarray(k_hash)
+    """Key-tile range ``[start, end)`` per query tile under the hash rule (paper Sec. 3.2, Alg. 2), on the
+    bucket-sorted vectors of ONE segment.  Buckets first: tiles all of whose keys lie in buckets below the
+    query tile's lowest bucket are skipped (their number is ``start``), and the tiles that begin in a
+    bucket not above the query tile's highest one number ``end_hash``.  Causality second: inside
+    ``[start, end_hash)`` the range stops after the last tile whose earliest key is not later than the
+    tile's latest query; when no tile qualifies the paper's rule leaves the range at ``end_hash``."""
+    _, q_last = _per_tile(q_idx, Bm)
+    qh_lo, qh_hi = _per_tile(q_hash, Bm)
+    k_first, _ = _per_tile(k_idx, Bn)
+    kh_lo, kh_hi = _per_tile(k_hash, Bn)
     out = []
-    for m0 in range(0, q_idx.shape[0], Bm):
-        qi = q_idx[m0:m0 + Bm]; qh = q_hash[m0:m0 + Bm]
-        start = 0; end_hash = 0
-        for n0 in range(0, k_idx.shape[0], Bn):
-            kh = k_hash[n0:n0 + Bn]
-            if kh.min() <= qh.max():
-                end_hash += 1
-            if kh.max() < qh.min():
-                start += 1
-        end = end_hash
-        for j in range(start, end_hash):
-            ki = k_idx[j * Bn:(j + 1) * Bn]
-            if ki.min() <= qi.max():
-                end = j + 1
-        out.append((start, end))
+    for i in range(q_last.shape[0]):
+        start = int(np.count_nonzero(kh_hi < qh_lo[i]))
+        end_hash = int(np.count_nonzero(kh_lo <= qh_hi[i]))
+        seen = np.flatnonzero(k_first[start:end_hash] <= q_last[i])
+        out.append((start, start + int(seen[-1]) + 1 if seen.size else end_hash))
     return out
 
 

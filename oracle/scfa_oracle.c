@@ -5,7 +5,7 @@
  * against.  It is never linked into, imported by, or called from the product
  * path; it shares no code, header, table or helper with the HIP sources.
  *
- * What it computes (paper Sec. 3, "implements the exact computation"): the
+ * What it computes (paper Sec. 3: the method is exact, not an approximation): the
  * method's result is exact softmax attention restricted to a mask, so the
  * oracle is that definition written out on the ORIGINAL, unpermuted tensors,
  * in double precision, with a two-pass softmax per row.  It never sorts,

@@ -36,9 +36,14 @@ FLAGS = [
 ]
 
 
+# the argument checks of the C ABI test for NaN: that file keeps IEEE semantics
+HONOR_NANS = {"scfa_api.hip"}
+
+
 def _compile(src: str, extra) -> str:
     obj = os.path.join(OBJ_DIR, src.replace(".hip", ".o"))
-    cmd = [HIPCC, *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
+    flags = [f for f in FLAGS if not (src in HONOR_NANS and f == "-fno-honor-nans")]
+    cmd = [HIPCC, *flags, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     # the host pass warns that it does not know the packed-fp32 feature: harmless
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)

@@ -62,6 +62,7 @@ static int check_attn_common(const void* q, const void* k, const void* v, const 
     if (!q || !k || !v || !q_key || !k_key || !work) return SCFA_EINVAL;
     if (B <= 0 || H <= 0 || T <= 0 || n_work <= 0) return SCFA_EINVAL;
     if (T > SCFA_MAX_T) return SCFA_EUNSUPPORTED;   // positions take the low 24 bits of a sort key
+    if ((long long)T * d * 4 > 0x7fffffffLL) return SCFA_EUNSUPPORTED;   // byte offsets inside a segment are 32-bit
     if (!(sm_scale > 0.f) || !isfinite(sm_scale)) return SCFA_EINVAL;
     if (!aligned16(q) || !aligned16(k) || !aligned16(v)) return SCFA_EINVAL;
     if ((flags & ~SCFA_FLAG_STRICT_CAUSAL) != 0) return SCFA_EUNSUPPORTED;
@@ -132,7 +133,7 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const uint
         rc = launch_zero_rows(reinterpret_cast<const int32_t*>(k_key), n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
         if (rc != SCFA_OK) return rc;
     }
-    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, qkdrop ? n_q : nullptr, S, T, d, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
+    rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, qkdrop ? n_q : nullptr, S, T, d, sm_scale, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
     rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, d,
                                    sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
@@ -241,7 +242,7 @@ int scfa_lsh_buckets(const void* x_q, const void* x_k, const float* R, int S, in
 int scfa_gather_rows(const void* x, const int32_t* idx, const int32_t* count, int S, int T, int d, int dtype,
                      int out_dtype, float scale, void* out, void* stream)
 {
-    if (!x || !idx || !out || S <= 0 || T <= 0 || d <= 0 || !(scale == scale)) return SCFA_EINVAL;
+    if (!x || !idx || !out || S <= 0 || T <= 0 || d <= 0 || !isfinite(scale)) return SCFA_EINVAL;
     if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
     if (out_dtype != dtype && !(dtype == SCFA_BF16 && out_dtype == SCFA_F16)) return SCFA_EUNSUPPORTED;
     if (scale != 1.0f && dtype == SCFA_BF16 && out_dtype == SCFA_BF16) return SCFA_EUNSUPPORTED;   // bf16 copies are bit-exact only
@@ -261,7 +262,7 @@ int scfa_gather_qkv(const void* q, const void* k, const void* v, const int32_t* 
                     float q_scale, void* q_out, void* k_out, void* v_out, void* stream)
 {
     if (!q || !k || !v || !q_idx || !k_idx || !q_out || !k_out || !v_out || S <= 0 || T <= 0 || d <= 0 ||
-        !(q_scale == q_scale))
+        !isfinite(q_scale))
         return SCFA_EINVAL;
     if (dtype != SCFA_BF16 && dtype != SCFA_F32) return SCFA_EUNSUPPORTED;
     if (out_dtype != dtype && !(dtype == SCFA_BF16 && out_dtype == SCFA_F16)) return SCFA_EUNSUPPORTED;

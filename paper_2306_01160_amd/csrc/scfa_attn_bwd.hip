@@ -1,6 +1,6 @@
 // Backward attention over the work lists, fp16 compute format, fp32 accumulation.
 //
-// The paper adapts the backward "in a similar fashion" to the forward (Sec. 3.1, 3.2):
+// The paper states that the backward is obtained the same way as the forward (Sec. 3.1, 3.2):
 // per block of keys, find the blocks of queries that can see it.  The gradients are those
 // of masked softmax attention with P recomputed from the saved logsumexp:
 //   P_ij = exp(tau s_ij - LSE_i),  dP_ij = <dO_i, V_j>,  D_i = <dO_i, O_i>,
@@ -17,22 +17,29 @@
 // magnitude lies in [1, 2) before it is converted to fp16; the gradients are multiplied
 // by the inverse power at the end.  Both scalings are exact.
 //
-// The operand a workgroup keeps in registers (its queries Q' in the dQ kernel, its keys K' in the
-// dK/dV kernel) is multiplied by tau * log2(e) once per work item and rounded to fp16, so the
-// score contraction is in base-2 units; the other operand streams through LDS as it is, so
-// dK = tau * dS^T Q and dQ = tau * dS K need no correction.  The per-row subtractions of
-// P = 2^(x - LSE log2 e) and dS = P (dP - D) are folded into the contractions:
-//   - where the row is a lane (dQ kernel) the accumulators start from -LSE log2 e and -D;
-//   - where the row is a register (dK/dV kernel) one more contraction step of 16 slots is
-//     appended: the pre-pass writes, per query, LSE log2 e and D split into three fp16
-//     pieces each (an 8-element "aux" row, pieces 2 and 3 scaled by 2^11), and the key side
-//     of that step is the constant (-1, -2^-11, -2^-11, 0 | 0, 0, 0, 0) for the score
-//     and (0, 0, 0, 0 | -1, -2^-11, -2^-11, 0) for dP.  Products of fp16 numbers are exact
-//     in the fp32 accumulation, so the split only costs the final fp32 rounding.
-// What is left per element is one exponential, one product and the fp16 packing.  The dK/dV
-// kernel needs both P and dS in fp16, so it packs P and dP - D and multiplies the packed
-// pairs (v_pk_mul_f16: half an instruction per element, one more fp16 rounding in dS); P <= 1
-// keeps that product finite for any finite |dP - D| below the fp16 range.
+// Queries, keys, values and dO are contracted as they are (the inputs' own values, like the forward),
+// so the recomputed scores are the exact <q, k> up to fp32 accumulation and the softmax scale enters per
+// element in fp32: P = 2^(tau log2(e) s - LSE log2 e).  (An earlier form folded tau log2(e) into the
+// register-resident operand, rounded to fp16: one instruction per element less, but a relative 2^-12 per
+// element of the scores, which at logits in the hundreds -- one outlier key row is enough -- put errors
+// of 5 - 25 % into the gradients.)  The per-row subtractions of P and dS = P (dP - D) are folded into the
+// contractions:
+//   - where the row is a lane (dQ kernel) the exponent is one fused multiply-add with the per-lane
+//     constant -LSE log2 e, and the dP accumulators start from -D;
+//   - where the row is a register (dK/dV kernel) one more contraction step of 16 slots is appended:
+//     the pre-pass writes, per query, LSE in raw-score units (LSE / tau) and D split into three fp16
+//     pieces each (an 8-element "aux" row, see split3), and the key side of that step is the constant
+//     (-2^5, -2^-5, -2^-14, 0 | 0, 0, 0, 0) for the score and (0, 0, 0, 0 | -1, -2^-11, -2^-11, 0)
+//     for dP.  Products of fp16 numbers are exact in the fp32 accumulation, so the split only costs
+//     the final fp32 rounding; the exponent is then one multiplication by tau log2(e).
+// What is left per element is that multiplication (or fused multiply-add), one exponential, one
+// product and the fp16 packing.  The dK/dV kernel needs both P and dS in fp16, so it packs P and
+// dP - D and multiplies the packed pairs (v_pk_mul_f16: half an instruction per element, one more
+// fp16 rounding in dS); P <= 1 keeps that product finite for any finite |dP - D| below the fp16 range.
+//
+// Range.  Values beyond the fp16 range arrive as infinities (the gather converts with IEEE rules), and a
+// logsumexp or D beyond what the aux rows hold becomes infinite there: in all these cases the gradients
+// come out non-finite rather than finite and wrong.
 #include "scfa_common.hpp"
 #include "scfa_mma.hpp"
 
@@ -98,18 +105,22 @@ __device__ __forceinline__ void pow2_scales(uint32_t amax_bits, float& scale, fl
     inv_scale = __uint_as_float((uint32_t)e << 23);          // 2^(e-127)
 }
 
-// x (clamped to +-AUX_LIMIT) = h1 + 2^-11 h2 + 2^-11 h3 with fp16 h1, h2, h3, to about 33 bits;
-// packed as (h1, h2), (h3, 0).  Every piece stays in the normal fp16 range or is negligible.
-constexpr float AUX_LIMIT = 60000.f;
-constexpr float AUX_PIECE = 2048.f;   // 2^11
-__device__ __forceinline__ void split3(float x, uint32_t& w01, uint32_t& w23)
+// x = a1 h1 + a2 h2 + a3 h3 with fp16 h1, h2, h3 and powers of two a1 >= a2 >= a3 (all normal fp16 numbers), to
+// about 33 bits; packed as (h1, h2), (h3, 0).  The residuals are exact in fp32, so a piece that rounds (or
+// underflows) is made up for by the next one.  |x| beyond 65504 a1 makes h1 infinite and the gradients of that
+// row non-finite: out of the kernels' range, and visibly so.  D (after the scaling of dO) uses (1, 2^-11, 2^-11):
+// range 65504.  The logsumexp is stored in units of the raw scores <q, k>, LSE log2(e) / (tau log2(e)), i.e.
+// about LSE / tau: (2^5, 2^-5, 2^-14) reach 2.09e6, logits of +-2.6e5 at tau = 1/8.
+constexpr float AUX_D1 = 1.f, AUX_D2 = 1.f / 2048.f, AUX_D3 = 1.f / 2048.f;
+constexpr float AUX_L1 = 32.f, AUX_L2 = 1.f / 32.f, AUX_L3 = 1.f / 16384.f;
+constexpr float AUX_L_NO_KEYS = 2.0e6f;   // stands for LSE = -inf (a row without keys): every probability becomes 0
+__device__ __forceinline__ void split3(float x, float a1, float a2, float a3, uint32_t& w01, uint32_t& w23)
 {
-    x = fminf(fmaxf(x, -AUX_LIMIT), AUX_LIMIT);
-    const _Float16 h1 = (_Float16)x;
-    const float r1 = x - (float)h1;                       // exact
-    const _Float16 h2 = (_Float16)(r1 * AUX_PIECE);
-    const float r2 = r1 - (float)h2 * (1.f / AUX_PIECE);  // exact
-    const _Float16 h3 = (_Float16)(r2 * AUX_PIECE);
+    const _Float16 h1 = (_Float16)(x * (1.f / a1));
+    const float r1 = x - (float)h1 * a1;                  // exact
+    const _Float16 h2 = (_Float16)(r1 * (1.f / a2));
+    const float r2 = r1 - (float)h2 * a2;                 // exact
+    const _Float16 h3 = (_Float16)(r2 * (1.f / a3));
     w01 = (uint32_t)__builtin_bit_cast(uint16_t, h1) | ((uint32_t)__builtin_bit_cast(uint16_t, h2) << 16);
     w23 = (uint32_t)__builtin_bit_cast(uint16_t, h3);
 }
@@ -120,7 +131,7 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     const uint16_t* __restrict__ o, const uint16_t* __restrict__ o_f16, const float* __restrict__ lse,
     const uint16_t* __restrict__ d_o, const uint32_t* __restrict__ q_key, const int32_t* __restrict__ n_q,
     const uint32_t* __restrict__ amax_partial,
-    int n_partial, int T, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
+    int n_partial, int T, float inv_cexp, uint16_t* __restrict__ do_perm, float* __restrict__ delta_perm, float* __restrict__ lse_perm,
     uint16_t* __restrict__ aux_perm, float* __restrict__ inv_scale_out)
 {
     constexpr int LPR = D / 8;   // lanes per row
@@ -182,18 +193,18 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
         const float lse_r = lse[seg + src];
         delta_perm[seg + r] = acc;
         lse_perm[seg + r] = lse_r;
-        // a row without keys gets an exponent offset that makes every probability 0
-        const float l2 = lse_r != -INFINITY ? fmaf(lse_r, LOG2E, -RTZ_BIAS_LOG2) : AUX_LIMIT;
+        // LSE in raw-score units; a row without keys gets an offset that makes every probability 0
+        const float l_raw = lse_r != -INFINITY ? fmaf(lse_r, LOG2E, -RTZ_BIAS_LOG2) * inv_cexp : AUX_L_NO_KEYS;
         uint32_t w[4];
-        split3(l2, w[0], w[1]);
-        split3(acc, w[2], w[3]);
+        split3(l_raw, AUX_L1, AUX_L2, AUX_L3, w[0], w[1]);
+        split3(acc, AUX_D1, AUX_D2, AUX_D3, w[2], w[3]);
         *reinterpret_cast<uint4*>(aux_perm + (seg + r) * 8) = make_uint4(w[0], w[1], w[2], w[3]);
     }
 }
 
 int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const uint32_t* q_key,
                          const int32_t* n_q,
-                         int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
+                         int S, int T, int d, float tau, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_PREP, st);
@@ -205,10 +216,10 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
     dim3 grid((unsigned)((threads + 255) / 256), S), block(256);
     if (d == 64)
         hipLaunchKernelGGL(bwd_prep_kernel<64>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
-                           q_key, n_q, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_key, n_q, amax, (int)nblk, T, 1.f / (tau * LOG2E), (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else if (d == 128)
         hipLaunchKernelGGL(bwd_prep_kernel<128>, grid, block, 0, st, (const uint16_t*)o, (const uint16_t*)o_f16, lse, (const uint16_t*)d_o,
-                           q_key, n_q, amax, (int)nblk, T, (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
+                           q_key, n_q, amax, (int)nblk, T, 1.f / (tau * LOG2E), (uint16_t*)do_perm, delta_perm, lse_perm, (uint16_t*)aux_perm, inv_scale);
     else
         return SCFA_EUNSUPPORTED;
     SCFA_HIP_TRY(hipGetLastError());
@@ -265,6 +276,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
+    const float cexp = tau * LOG2E;   // scores are raw <q, k> sums minus LSE in the same units: P = 2^(cexp x)
     const int krow = wave * 32 + l32;
     const bool kvalid = krow < k_count;
     const int kr = min(krow, k_count - 1);            // keys past the end repeat the last one; never written
@@ -280,7 +292,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         const uint16_t* vp = v + (seg + k_begin + kr) * D + h * 8;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-            kf[kk] = scale_f16x8(as_f16x8(*reinterpret_cast<const uint4*>(kp + kk * 16)), tau * LOG2E);   // Q K'^T: base-2 scores
+            kf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(kp + kk * 16));
             vf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(vp + kk * 16));
         }
 #pragma unroll
@@ -290,11 +302,11 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     // key side of the appended contraction step (lanes 32-63 hold slots 8-15: all zero)
     f16x8 sub_lse, sub_delta;
     {
-        const _Float16 one = h == 0 ? (_Float16)-1.f : (_Float16)0.f;
-        const _Float16 piece = h == 0 ? (_Float16)(-1.f / AUX_PIECE) : (_Float16)0.f;
         const _Float16 z = (_Float16)0.f;
-        sub_lse = f16x8{one, piece, piece, z, z, z, z, z};
-        sub_delta = f16x8{z, z, z, z, one, piece, piece, z};
+        const _Float16 l1 = h == 0 ? (_Float16)-AUX_L1 : z, l2 = h == 0 ? (_Float16)-AUX_L2 : z, l3 = h == 0 ? (_Float16)-AUX_L3 : z;
+        const _Float16 d1 = h == 0 ? (_Float16)-AUX_D1 : z, d2 = h == 0 ? (_Float16)-AUX_D2 : z, d3 = h == 0 ? (_Float16)-AUX_D3 : z;
+        sub_lse = f16x8{l1, l2, l3, z, z, z, z, z};
+        sub_delta = f16x8{z, z, z, z, d1, d2, d3, z};
         touch(sub_lse); touch(sub_delta);
     }
 
@@ -396,7 +408,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
                 }
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    float p = fast_exp2(sacc[qb][4 * g + e]);
+                    float p = fast_exp2(sacc[qb][4 * g + e] * cexp);
                     if (MASKED) { if (qpa[e] - klo > kspan) p = 0.f; }     // bucket and causal test on the sort keys
                     sacc[qb][4 * g + e] = p;
                 }
@@ -563,6 +575,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
     const bool some = qvalid && qpos - strict >= 0;
     const uint32_t qlo = some ? (qkey & ~KEY_POS_MASK) : KEY_NEVER;
     const uint32_t qspan = some ? (uint32_t)(qpos - strict) : 0u;
+    const float cexp = tau * LOG2E;   // scores are raw <q, k> sums: P = 2^(cexp s - LSE log2 e), one fma per element
     const float lse_ld = lse_perm[seg + q_begin + qr];
     const float lse2 = (qvalid && lse_ld != -INFINITY) ? fmaf(lse_ld, LOG2E, -RTZ_BIAS_LOG2) : INFINITY;
     const float delta = delta_perm[seg + q_begin + qr];
@@ -573,18 +586,18 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
         const uint16_t* gp = do_perm + (seg + q_begin + qr) * D + h * 8;
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) {
-            qf[kk] = scale_f16x8(as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16)), tau * LOG2E);   // K Q'^T: base-2 scores
+            qf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(qp + kk * 16));
             gf[kk] = as_f16x8(*reinterpret_cast<const uint4*>(gp + kk * 16));
         }
 #pragma unroll
         for (int kk = 0; kk < D / 16; ++kk) { touch(qf[kk]); touch(gf[kk]); }
     }
 
-    f32x16 dqacc[D / 32], s_start, p_start;   // loop-invariant accumulator starts: -LSE log2 e, -D
+    f32x16 dqacc[D / 32], p_start;   // loop-invariant accumulator start of dP: -D
 #pragma unroll
     for (int db = 0; db < D / 32; ++db) dqacc[db] = zero16();
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s_start[i] = -lse2; p_start[i] = -delta; }
+    for (int i = 0; i < 16; ++i) p_start[i] = -delta;
 
     const int n_tiles = (k_count + BN - 1) / BN;
     const int n_free = min(k_nomask / BN, n_tiles);
@@ -628,13 +641,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
             f32x16 sacc[KBS], pacc[KBS];
 #pragma unroll
             for (int kb = 0; kb < KBS; ++kb) {
+                sacc[kb] = zero16();
                 if (KBS == 2) {
-                    sacc[kb] = s_start; pacc[kb] = p_start;     // read as the C operand of the first MFMA: no moves
+                    pacc[kb] = p_start;                         // read as the C operand of the first MFMA: no moves
                 } else {                                        // registers are scarcer than moves at d = 128
-                    float s0 = s_start[0], p0 = p_start[0];
-                    asm volatile("" : "+v"(s0), "+v"(p0));      // not a loop invariant: splat here, every time
+                    float p0 = p_start[0];
+                    asm volatile("" : "+v"(p0));                // not a loop invariant: splat here, every time
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) { sacc[kb][i] = s0; pacc[kb][i] = p0; }
+                    for (int i = 0; i < 16; ++i) pacc[kb][i] = p0;
                 }
             }
 #pragma unroll
@@ -656,7 +670,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
                     }
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
-                        float p = fast_exp2(sacc[kb][4 * g + e]);
+                        float p = fast_exp2(fmaf(sacc[kb][4 * g + e], cexp, -lse2));
                         if (MASKED) { if (kpa[e] - qlo > qspan) p = 0.f; }     // bucket and causal test on the sort keys
                         pacc[kb][4 * g + e] = p * pacc[kb][4 * g + e];
                     }

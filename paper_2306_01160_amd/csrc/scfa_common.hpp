@@ -100,7 +100,7 @@ int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const uint
                          float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st);
 int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const uint32_t* q_key,
                          const int32_t* n_q,
-                         int S, int T, int d, void* do_perm, float* delta_perm, float* lse_perm,
+                         int S, int T, int d, float tau, void* do_perm, float* delta_perm, float* lse_perm,
                          void* aux_perm, uint32_t* amax, float* inv_scale, hipStream_t st);
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,

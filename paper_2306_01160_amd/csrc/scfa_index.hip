@@ -316,8 +316,9 @@ struct GatherProblem {
 struct GatherBatch { GatherProblem p[3]; };
 
 // MODE 0: bit-exact copy; 1: bf16 -> fp16 (times scale, one rounding to nearest even; with
-// scale 1 exact for magnitudes in [2^-17, 65504], larger results saturate to the largest
-// fp16); 2: fp32 times scale (one rounding)
+// scale 1 exact for magnitudes in [2^-17, 65504], larger ones become infinite and NaN stays
+// NaN, so that an input outside the compute format shows in the results instead of being
+// replaced by a finite value); 2: fp32 times scale (one rounding)
 template <int MODE>
 __global__ __launch_bounds__(256) void gather_rows_kernel(GatherBatch batch, int T, int chunks_per_row)
 {
@@ -336,10 +337,8 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(GatherBatch batch, int
         uint32_t o[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float lo = __uint_as_float(w[i] << 16) * pr.scale, hi = __uint_as_float(w[i] & 0xffff0000u) * pr.scale;
-            lo = fminf(fmaxf(lo, -65504.f), 65504.f);
-            hi = fminf(fmaxf(hi, -65504.f), 65504.f);
-            const _Float16 a = (_Float16)lo, b = (_Float16)hi;
+            const float lo = __uint_as_float(w[i] << 16) * pr.scale, hi = __uint_as_float(w[i] & 0xffff0000u) * pr.scale;
+            const _Float16 a = (_Float16)lo, b = (_Float16)hi;   // IEEE conversion: beyond the fp16 range -> inf, NaN stays NaN
             o[i] = (uint32_t)__builtin_bit_cast(uint16_t, a) | ((uint32_t)__builtin_bit_cast(uint16_t, b) << 16);
         }
         res = make_uint4(o[0], o[1], o[2], o[3]);

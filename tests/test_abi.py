@@ -58,6 +58,14 @@ def test_argument_checks_reject_before_any_launch():
     assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 48, 0, 0.125, 0, one, one, None, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, -1.0, 0, one, one, None, None) == binding.SCFA_EINVAL
     assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, 0.125, 2, one, one, None, None) == binding.SCFA_EUNSUPPORTED   # unknown flag bit
+    # non-finite scalars are rejected (the checks must survive the kernels' fast-math flags)
+    nan, inf = float("nan"), float("inf")
+    for bad in (nan, inf, -inf, 0.0):
+        assert L.scfa_hash_attn_fwd(one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, bad, 0, one, one, None, None) == binding.SCFA_EINVAL
+        assert L.scfa_qkdrop_attn_fwd(one, one, one, one, one, one, one, 1, 1, 1, 8, 64, 0, bad, 0, one, one, None, None) == binding.SCFA_EINVAL
+    for bad in (nan, inf):
+        assert L.scfa_gather_rows(one, one, None, 1, 8, 64, 0, 2, bad, one, None) == binding.SCFA_EINVAL
+        assert L.scfa_gather_qkv(one, one, one, one, one, None, None, 1, 8, 64, 0, 2, bad, one, one, one, None) == binding.SCFA_EINVAL
     ws = ctypes.c_void_p(256)
     assert L.scfa_hash_attn_bwd(one, one, one, one, one, one, 1, one, 1, one, None, one, one, 1, 1, 8, 64, 0, 0.125, 0,
                                 one, one, one, ws, 16, None) == binding.SCFA_EWORKSPACE
