@@ -191,10 +191,13 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(
     for (int off = LPR / 2; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
     if (valid && c8 == 0) {
         const float lse_r = lse[seg + src];
-        delta_perm[seg + r] = acc;
-        lse_perm[seg + r] = lse_r;
         // LSE in raw-score units; a row without keys gets an offset that makes every probability 0
         const float l_raw = lse_r != -INFINITY ? fmaf(lse_r, LOG2E, -RTZ_BIAS_LOG2) * inv_cexp : AUX_L_NO_KEYS;
+        // beyond what the aux pieces hold the dK/dV kernel sees infinities; the dQ kernel, which reads these
+        // fp32 copies, is given an infinite D so that both report the row as out of range
+        const bool out_of_range = fabsf(l_raw) > 65504.f * AUX_L1 || fabsf(acc) > 65504.f * AUX_D1;
+        delta_perm[seg + r] = out_of_range ? INFINITY : acc;
+        lse_perm[seg + r] = lse_r;
         uint32_t w[4];
         split3(l_raw, AUX_L1, AUX_L2, AUX_L3, w[0], w[1]);
         split3(acc, AUX_D1, AUX_D2, AUX_D3, w[2], w[3]);

@@ -126,3 +126,20 @@ def test_nan_in_an_input_reaches_the_output():
     sees = (lq[0] == lk[0, 50]) & (np.arange(wl.T) >= 50)
     assert np.isnan(og[0][sees]).any(axis=1).all(), "NaN in a key must show in every row that attends it"
     assert np.isfinite(og[1]).all()                                  # the other segment is untouched
+
+
+def test_logits_beyond_the_backward_range_give_non_finite_gradients():
+    """everything scaled by 2^8: logits of ~3e5, |LSE| / tau beyond what the backward's aux rows hold.  The forward
+    is still exact (one-hot softmax); the gradients must not come back finite."""
+    wl = _scaled(_base(64, "hash"), 256.0, 256.0, 256.0, 256.0)
+    got, ref, lg, L_ref = _errors(wl)
+    fin = np.isfinite(L_ref)
+    assert np.abs(L_ref[fin]).max() * 8 > 2.1e6                       # the case is out of range
+    assert np.all(np.abs(lg[fin] - L_ref[fin]) <= 4 * np.spacing(np.abs(L_ref[fin]).astype(np.float32)))
+    assert float(np.abs(got["O"] - ref["O"]).max()) <= REL["O"] * float(np.abs(ref["O"]).max())
+    big = fin & (np.abs(np.where(fin, L_ref, 0.0)) * 8 > 2.2e6)       # rows clearly beyond the range (LSE / tau, tau = 1/8)
+    assert big.sum() >= 4
+    for n in ("dQ",):
+        g = got[n]
+        assert not np.isfinite(g[big]).all(axis=-1).any(), f"{n}: an out-of-range row came back finite"
+    assert not np.isfinite(got["dK"]).all() and not np.isfinite(got["dV"]).all()
