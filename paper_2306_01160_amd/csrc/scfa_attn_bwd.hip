@@ -542,8 +542,10 @@ struct DqRing {
     static constexpr int NBUF = D == 64 ? 3 : 2;
 };
 
+// Two wavefronts per SIMD are asked for explicitly: at d = 128 the register allocator would otherwise take a
+// few AccVGPRs beyond 256 registers and halve the occupancy.
 template <int D>
-__global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void attn_bwd_dq_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
     const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
@@ -654,14 +656,45 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
                     for (int i = 0; i < 16; ++i) pacc[kb][i] = p0;
                 }
             }
+            if (KBS == 1) {
+                // two wavefronts per SIMD do not hide the LDS latency of a read issued at its use: the row
+                // fragments of a contraction step are requested one step (two matrix instructions) ahead
+                f16x8 fk[2], fv[2];
+                fk[0] = swz_rows<D>(Kt, k0 * 32 + l32, h * 8);
+                fv[0] = swz_rows<D>(Vt, k0 * 32 + l32, h * 8);
 #pragma unroll
-            for (int kk = 0; kk < D / 16; ++kk)
-#pragma unroll
-                for (int kb = 0; kb < KBS; ++kb) {
-                    sacc[kb] = mfma16(swz_rows<D>(Kt, (k0 + kb) * 32 + l32, kk * 16 + h * 8), qf[kk], sacc[kb]);
-                    pacc[kb] = mfma16(swz_rows<D>(Vt, (k0 + kb) * 32 + l32, kk * 16 + h * 8), gf[kk], pacc[kb]);
+                for (int kk = 0; kk < D / 16; ++kk) {
+                    if (kk + 1 < D / 16) {
+                        fk[(kk + 1) & 1] = swz_rows<D>(Kt, k0 * 32 + l32, (kk + 1) * 16 + h * 8);
+                        fv[(kk + 1) & 1] = swz_rows<D>(Vt, k0 * 32 + l32, (kk + 1) * 16 + h * 8);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    sacc[0] = mfma16(fk[kk & 1], qf[kk], sacc[0]);
+                    pacc[0] = mfma16(fv[kk & 1], gf[kk], pacc[0]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+            } else {
+#pragma unroll
+                for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+                    for (int kb = 0; kb < KBS; ++kb) {
+                        sacc[kb] = mfma16(swz_rows<D>(Kt, (k0 + kb) * 32 + l32, kk * 16 + h * 8), qf[kk], sacc[kb]);
+                        pacc[kb] = mfma16(swz_rows<D>(Vt, (k0 + kb) * 32 + l32, kk * 16 + h * 8), gf[kk], pacc[kb]);
+                    }
+            }
 
+            // d = 128: the transposed K fragments of the first 16-key chunk are requested before the
+            // exponentials, those of the second chunk while the first chunk's products run
+            f16x8 tk[2][KBS == 1 ? D / 32 : 1];
+            if (KBS == 1) {
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) {
+                    int oa, ob;
+                    swz_trans_offsets<D>(2 * k0 * 16, db * 32, lane, oa, ob);
+                    tk[0][db] = swz_trans(Kt, oa, ob);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int kb = 0; kb < KBS; ++kb)
 #pragma unroll
@@ -679,18 +712,35 @@ __global__ __launch_bounds__(256) void attn_bwd_dq_f16_kernel(
                     }
                 }
 
-#pragma unroll
-            for (int c = 0; c < 2 * KBS; ++c) {
-                const int c4 = 2 * k0 + c;       // 16-key chunk of the tile
-                const f16x8 sf = pack_chunk(pacc[c >> 1], c & 1);
+            if (KBS == 1) {
+                const f16x8 sf0 = pack_chunk(pacc[0], 0), sf1 = pack_chunk(pacc[0], 1);
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int db = 0; db < D / 32; ++db) {
                     int oa, ob;
-                    swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
-                    dqacc[db] = mfma16(swz_trans(Kt, oa, ob), sf, dqacc[db]);
+                    swz_trans_offsets<D>((2 * k0 + 1) * 16, db * 32, lane, oa, ob);
+                    tk[1][db] = swz_trans(Kt, oa, ob);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) dqacc[db] = mfma16(tk[0][db], sf0, dqacc[db]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) dqacc[db] = mfma16(tk[1][db], sf1, dqacc[db]);
+                __builtin_amdgcn_sched_barrier(0);   // keep the two blocks apart
+            } else {
+#pragma unroll
+                for (int c = 0; c < 2 * KBS; ++c) {
+                    const int c4 = 2 * k0 + c;       // 16-key chunk of the tile
+                    const f16x8 sf = pack_chunk(pacc[c >> 1], c & 1);
+#pragma unroll
+                    for (int db = 0; db < D / 32; ++db) {
+                        int oa, ob;
+                        swz_trans_offsets<D>(c4 * 16, db * 32, lane, oa, ob);
+                        dqacc[db] = mfma16(swz_trans(Kt, oa, ob), sf, dqacc[db]);
+                    }
                 }
             }
-            if (KBS == 1) __builtin_amdgcn_sched_barrier(0);   // keep the two blocks apart
         }
     };
 
