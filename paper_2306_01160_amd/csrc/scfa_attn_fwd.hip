@@ -63,7 +63,7 @@ struct FwdRing {
 };
 
 template <int D, int NW, int QB>
-__global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2))) void attn_fwd_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
@@ -188,14 +188,35 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int b = 0; b < QB; ++b) sacc[kb][b] = start[b];
+        if (D == 128) {
+            // two wavefronts per SIMD do not hide the LDS latency of a read issued at its use: the K row
+            // fragments of a contraction step are requested one step ahead
+            f16x8 fk[2][2];
+            fk[0][0] = swz_rows<D>(Kt, l32, h * 8);
+            fk[0][1] = swz_rows<D>(Kt, 32 + l32, h * 8);
 #pragma unroll
-        for (int kk = 0; kk < D / 16; ++kk)
+            for (int kk = 0; kk < D / 16; ++kk) {
+                if (kk + 1 < D / 16) {
+                    fk[(kk + 1) & 1][0] = swz_rows<D>(Kt, l32, (kk + 1) * 16 + h * 8);
+                    fk[(kk + 1) & 1][1] = swz_rows<D>(Kt, 32 + l32, (kk + 1) * 16 + h * 8);
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const f16x8 a = swz_rows<D>(Kt, kb * 32 + l32, kk * 16 + h * 8);
+                for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int b = 0; b < QB; ++b) sacc[kb][b] = mfma16(a, qf[b][kk], sacc[kb][b]);
+                    for (int b = 0; b < QB; ++b) sacc[kb][b] = mfma16(fk[kk & 1][kb], qf[b][kk], sacc[kb][b]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        } else {
+#pragma unroll
+            for (int kk = 0; kk < D / 16; ++kk)
+#pragma unroll
+                for (int kb = 0; kb < 2; ++kb) {
+                    const f16x8 a = swz_rows<D>(Kt, kb * 32 + l32, kk * 16 + h * 8);
+#pragma unroll
+                    for (int b = 0; b < QB; ++b) sacc[kb][b] = mfma16(a, qf[b][kk], sacc[kb][b]);
+                }
+        }
 
         if (MASKED) {   // bucket and causal test in one range test on the sort keys
 #pragma unroll
@@ -308,14 +329,33 @@ __global__ __launch_bounds__(NW * 64) void attn_fwd_f16_kernel(
         for (int b = 0; b < QB; ++b) lsum[b] += lt[b];
 
         // O^T += V^T P^T
+        if (D == 128) {   // the V^T fragments of a 16-key chunk are requested while the previous chunk's products run
+            f16x8 fv[2][D / 32];
 #pragma unroll
-        for (int c4 = 0; c4 < 4; ++c4)
+            for (int db = 0; db < D / 32; ++db) fv[0][db] = swz_trans(Vt, v_off[0][db][0], v_off[0][db][1]);
 #pragma unroll
-            for (int db = 0; db < D / 32; ++db) {
-                const f16x8 a = swz_trans(Vt, v_off[c4][db][0], v_off[c4][db][1]);
+            for (int c4 = 0; c4 < 4; ++c4) {
+                if (c4 + 1 < 4) {
 #pragma unroll
-                for (int b = 0; b < QB; ++b) oacc[b][db] = mfma16(a, pf[b][c4], oacc[b][db]);
+                    for (int db = 0; db < D / 32; ++db) fv[(c4 + 1) & 1][db] = swz_trans(Vt, v_off[c4 + 1][db][0], v_off[c4 + 1][db][1]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                    for (int b = 0; b < QB; ++b) oacc[b][db] = mfma16(fv[c4 & 1][db], pf[b][c4], oacc[b][db]);
+                __builtin_amdgcn_sched_barrier(0);
             }
+        } else {
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4)
+#pragma unroll
+                for (int db = 0; db < D / 32; ++db) {
+                    const f16x8 a = swz_trans(Vt, v_off[c4][db][0], v_off[c4][db][1]);
+#pragma unroll
+                    for (int b = 0; b < QB; ++b) oacc[b][db] = mfma16(a, pf[b][c4], oacc[b][db]);
+                }
+        }
     };
 
 #pragma unroll
