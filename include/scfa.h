@@ -128,6 +128,18 @@ int scfa_sort_by_bucket_static(const int32_t *bucket, int S, int T, int nb,
                                int32_t *bucket_off_out, uint32_t *sort_key_out,
                                void *stream);
 
+/* Validating mode for the bucket ids (Sec. 3.2 takes ids in [0, nb) for granted; the sort
+ * clamps what lies outside so that it stays memory-safe, which hides a caller's mistake):
+ * counts the entries of `bucket` outside [0, nb).
+ *
+ *   bucket         [n] int32 (device), any shape flattened
+ *   n_invalid_out  [1] int32 (device): overwritten with the count (0 = every id is valid);
+ *                  the caller reads it when it wants to, the call does not synchronise
+ * Errors: SCFA_EINVAL for null pointers or n < 0; nb as for the sort.
+ */
+int scfa_count_invalid_buckets(const int32_t *bucket, long long n, int nb,
+                               int32_t *n_invalid_out, void *stream);
+
 /* The same sort for the query and the key bucket ids of one attention call in ONE
  * launch (Sec. 3.2 sorts both); outputs as above, one set per side.  The *_sorted_out
  * and *_sort_key_out pointers are nullable. */

@@ -27,7 +27,7 @@ KERNEL_IDS = {"sort": 0, "compact": 1, "gather": 2, "ranges": 3, "fwd": 4, "bwd_
 
 EXPORTS = [
     "scfa_version", "scfa_last_hip_error", "scfa_error_string", "scfa_sort_by_bucket", "scfa_sort_by_bucket_static",
-    "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv", "scfa_lsh_buckets",
+    "scfa_count_invalid_buckets", "scfa_sort_by_bucket_pair", "scfa_compact_keep_pair", "scfa_gather_qkv", "scfa_lsh_buckets",
     "scfa_compact_keep", "scfa_gather_rows", "scfa_block_ranges", "scfa_num_work_items",
     "scfa_tile_config", "scfa_hash_attn_fwd", "scfa_qkdrop_attn_fwd",
     "scfa_attn_bwd_workspace_bytes", "scfa_sort_workspace_bytes", "scfa_hash_attn_bwd", "scfa_qkdrop_attn_bwd",
@@ -55,6 +55,7 @@ def lib():
         L.scfa_error_string.argtypes = [ci]
         L.scfa_sort_by_bucket.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp, sz, vp]
         L.scfa_sort_by_bucket_static.argtypes = [vp, ci, ci, ci, vp, vp, vp, vp, vp]
+        L.scfa_count_invalid_buckets.argtypes = [vp, ctypes.c_longlong, ci, vp, vp]
         L.scfa_compact_keep.argtypes = [vp, ci, ci, vp, vp, vp, sz, vp]
         L.scfa_lsh_buckets.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, vp, vp, vp]
         L.scfa_sort_by_bucket_pair.argtypes = [vp, vp, ci, ci, ci, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
@@ -174,6 +175,14 @@ def scfa_sort_by_bucket_static(bucket: torch.Tensor, nb: int, idx: torch.Tensor,
     S, T = bucket.shape
     _check(lib().scfa_sort_by_bucket_static(_ptr(bucket), S, T, nb, _ptr(idx), _ptr(bsorted), _ptr(off), _ptr(key),
                                             _stream()), "scfa_sort_by_bucket_static")
+
+
+def scfa_count_invalid_buckets(bucket: torch.Tensor, nb: int) -> torch.Tensor:
+    """Number of ids outside [0, nb) as a one-element int32 device tensor (not synchronised)."""
+    out = torch.empty(1, dtype=torch.int32, device=bucket.device)
+    _check(lib().scfa_count_invalid_buckets(_ptr(bucket), bucket.numel(), nb, _ptr(out), _stream()),
+           "scfa_count_invalid_buckets")
+    return out
 
 
 def scfa_compact_keep(keep: torch.Tensor, use_ws=True):

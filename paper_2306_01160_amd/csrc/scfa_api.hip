@@ -182,6 +182,13 @@ int scfa_sort_by_bucket(const int32_t* bucket, int S, int T, int nb, int32_t* id
                                  nullptr, nullptr, nullptr, nullptr, ws, ws_bytes, (hipStream_t)stream);
 }
 
+int scfa_count_invalid_buckets(const int32_t* bucket, long long n, int nb, int32_t* n_invalid_out, void* stream)
+{
+    if (!bucket || !n_invalid_out || n < 0 || nb <= 0) return SCFA_EINVAL;
+    if (nb > SCFA_MAX_BUCKETS) return SCFA_EUNSUPPORTED;
+    return launch_count_invalid_buckets(bucket, n, nb, n_invalid_out, (hipStream_t)stream);
+}
+
 int scfa_sort_by_bucket_static(const int32_t* bucket, int S, int T, int nb, int32_t* idx_out,
                                int32_t* bucket_sorted_out, int32_t* bucket_off_out, uint32_t* sort_key_out,
                                void* stream)

@@ -77,6 +77,7 @@ constexpr int F32_TILE_N = 32;
 int launch_sort_by_bucket(int n_problems, const int32_t* bucket0, const int32_t* bucket1, int S, int T, int nb,
                           int32_t* idx0, int32_t* sorted0, int32_t* off0, uint32_t* key0, int32_t* idx1,
                           int32_t* sorted1, int32_t* off1, uint32_t* key1, void* ws, size_t ws_bytes, hipStream_t st);
+int launch_count_invalid_buckets(const int32_t* bucket, long long n, int nb, int32_t* counter, hipStream_t st);
 int launch_sort_by_bucket_static(const int32_t* bucket, int S, int T, int nb, int32_t* idx, int32_t* sorted,
                                  int32_t* off, uint32_t* key, hipStream_t st);
 int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,

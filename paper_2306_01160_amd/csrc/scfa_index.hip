@@ -370,6 +370,37 @@ int launch_gather_rows(int n_tensors, const void* const* x, const int32_t* const
 }
 
 // ---------------------------------------------------------------------------
+// Bucket ids outside [0, nb): counted, one atomic per wavefront that found any.  The first
+// kernel clears the counter (no memset node: the pair may be captured in a graph).
+__global__ void clear_counter_kernel(int32_t* __restrict__ counter) { *counter = 0; }
+
+__global__ __launch_bounds__(256) void count_invalid_buckets_kernel(const int32_t* __restrict__ bucket, long long n,
+                                                                    int nb, int32_t* __restrict__ counter)
+{
+    int bad = 0;
+    for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < n; i += (long long)gridDim.x * 256) {
+        const int b = bucket[i];
+        bad += (b < 0 || b >= nb) ? 1 : 0;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) bad += __shfl_xor(bad, off);
+    if ((threadIdx.x & 63) == 0 && bad > 0) atomicAdd(counter, bad);
+}
+
+int launch_count_invalid_buckets(const int32_t* bucket, long long n, int nb, int32_t* counter, hipStream_t st)
+{
+    hipLaunchKernelGGL(clear_counter_kernel, dim3(1), dim3(1), 0, st, counter);
+    SCFA_HIP_TRY(hipGetLastError());
+    if (n > 0) {
+        const long long blocks = (n + 256 * 8 - 1) / (256 * 8);
+        hipLaunchKernelGGL(count_invalid_buckets_kernel, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st,
+                           bucket, n, nb, counter);
+        SCFA_HIP_TRY(hipGetLastError());
+    }
+    return SCFA_OK;
+}
+
+// ---------------------------------------------------------------------------
 // Zero the rows idx[s, count[s] .. T) of up to two [S,T,row] outputs (original order)
 // and set vec[s, idx] = vec_value: the dropped queries / keys of QK-dropping.
 __global__ __launch_bounds__(256) void zero_rows_kernel(const int32_t* __restrict__ idx,

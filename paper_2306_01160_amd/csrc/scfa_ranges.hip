@@ -95,10 +95,11 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const Searched& b_
                            int tile_b, int n_items_max, int32_t* __restrict__ work_out,
                            long long* counters2, int32_t* s_tile_base, int32_t* s_unit_first, int32_t* s_cost)
 {
-    // Units (nb <= 256, one thread): a bucket with a tile or more of rows on the tiled side is a
-    // unit of its own; smaller consecutive buckets are taken together while their rows fit one
-    // tile.  A bucket without rows on the tiled side joins only if its other side is shorter than
-    // a tile (it would be computed for nothing).  Tiles per unit -> exclusive prefix.
+    // Units (nb <= 256, one thread): a bucket with a tile or more of rows on either side is a
+    // unit of its own (its items keep their causal range and mask-free prefix); consecutive buckets
+    // that are shorter than a tile on both sides are taken together while their rows on the tiled
+    // side fit one tile: only there does one item walk fewer tiles than one item per bucket would.
+    // Tiles per unit -> exclusive prefix.
     __shared__ int s_n_units;
     if (threadIdx.x == 0) {
         int acc = 0, u = 0, b = 0;
@@ -107,10 +108,10 @@ __device__ void build_list(const int32_t* __restrict__ a_idx, const Searched& b_
             s_tile_base[u] = acc;
             int rows = a_off[b + 1] - a_off[b];
             int e = b + 1;
-            const bool alone = rows >= tile_a || (rows == 0 && b_off[b + 1] - b_off[b] >= tile_b);
+            const bool alone = rows >= tile_a || b_off[b + 1] - b_off[b] >= tile_b;
             while (!alone && e < nb) {
                 const int r2 = a_off[e + 1] - a_off[e];
-                if (rows + r2 > tile_a || (r2 == 0 && b_off[e + 1] - b_off[e] >= tile_b)) break;
+                if (rows + r2 > tile_a || b_off[e + 1] - b_off[e] >= tile_b) break;
                 rows += r2;
                 ++e;
             }

@@ -42,6 +42,9 @@ def test_argument_checks_reject_before_any_launch():
     assert L.scfa_compact_keep(None, 1, 8, None, None, None, 0, None) == binding.SCFA_EINVAL
     assert L.scfa_gather_rows(None, None, None, 1, 8, 64, 0, 0, 1.0, None, None) == binding.SCFA_EINVAL
     one = ctypes.c_void_p(16)   # never dereferenced: checks fail first
+    assert L.scfa_count_invalid_buckets(None, 8, 2, one, None) == binding.SCFA_EINVAL
+    assert L.scfa_count_invalid_buckets(one, -1, 2, one, None) == binding.SCFA_EINVAL
+    assert L.scfa_count_invalid_buckets(one, 8, 100000, one, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_sort_by_bucket(one, 1, 8, 100000, one, one, one, None, None, 0, None) == binding.SCFA_EUNSUPPORTED
     assert L.scfa_sort_by_bucket(one, 0, 8, 2, one, one, one, None, None, 0, None) == binding.SCFA_EINVAL
     assert L.scfa_sort_by_bucket(one, 1, 1 << 24, 2, one, one, one, one, None, 0, None) == binding.SCFA_EUNSUPPORTED   # position does not fit a sort key

@@ -50,6 +50,21 @@ def test_sort_clamps_out_of_range_ids():
     assert np.array_equal(off.cpu().numpy(), roff)
 
 
+@pytest.mark.parametrize("shape,nb,n_bad", [((1, 6), 2, 3), ((3, 1000), 16, 0), ((4, 40000), 8, 1234), ((2, 1), 1, 1)])
+def test_count_invalid_buckets(shape, nb, n_bad):
+    """The validating call counts exactly the ids the sort would clamp."""
+    rng = np.random.default_rng(nb * 31 + n_bad)
+    b = rng.integers(0, nb, shape).astype(np.int32)
+    flat = b.reshape(-1)
+    where = rng.choice(flat.size, n_bad, replace=False)
+    flat[where] = np.where(rng.random(n_bad) < 0.5, -1 - rng.integers(0, 1000, n_bad), nb + rng.integers(0, 1000, n_bad))
+    got = sc.scfa_count_invalid_buckets(_t(b), nb)
+    assert int(got.item()) == int(((b < 0) | (b >= nb)).sum()) == n_bad
+    # the counter is overwritten, not accumulated
+    got2 = sc.scfa_count_invalid_buckets(_t(np.zeros(shape, np.int32)), nb)
+    assert int(got2.item()) == 0
+
+
 @pytest.mark.parametrize("S,T,p", [(1, 8, 0.5), (2, 1, 1.0), (3, 100, 0.0), (4, 2048, 0.5), (16, 32768, 0.3),
                                    (2, 5000, 1.0), (3, 777, 0.1)])
 def test_compact_keep_bit_exact(S, T, p):
