@@ -380,3 +380,20 @@ def test_hash_T65536_sampled():
     errs.update(compare_backward(wl, grads, segs=segs, q_rows=rows, k_rows=rows))
     print(wl.name, errs)
     assert_within(errs, wl.dtype)
+
+
+def test_hash_T262144_sampled():
+    """Four times the longest sequence of the sweep (B=1, H=1, T=262144, d=64, 128 uniformly random buckets):
+    byte offsets inside the segment pass 2^25, the sort runs in 64 chunks, the schedule holds 2176 items per
+    list; sampled rows against the oracle."""
+    T = 262144
+    wl = W.hash_uniform(66, 1, 1, T, 64, 128)
+    o, lse, grads, _ = run_gpu(wl)
+    rows = np.unique(np.concatenate([np.arange(0, 140), np.arange(200000, 200100), np.arange(T - 140, T),
+                                     np.random.default_rng(3).integers(0, T, 100)])).astype(np.int32)
+    segs = [0]
+    errs = compare_forward(wl, o, lse, segs=segs, rows=rows)
+    errs.update(compare_backward(wl, grads, segs=segs, q_rows=rows, k_rows=rows))
+    print(wl.name, errs)
+    assert_within(errs, wl.dtype)
+
