@@ -351,8 +351,166 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         }
     };
 
-    auto tile = [&](int buf, auto masked_tag) {
+    // The same loads one at a time (Q rounds, dO rounds, aux rows, positions), for the hand-ordered tile below, which
+    // issues them between its groups: the address unit takes 16 cycles per 64-lane load, the four wavefronts of a
+    // workgroup that all issue a tile's ten loads right after the barrier queue up behind each other, and with one
+    // wavefront per SIMD nobody computes meanwhile.
+    constexpr int ROUNDS = AsyncTile<D, BM, 256>::ROUNDS;
+    auto issue_part = [&](int jt, int buf, int part) __attribute__((always_inline)) {
+        const uint32_t base = lds0 + (uint32_t)(buf * BUF_BYTES);
+        if (part < ROUNDS) loader.load_round(q_desc, jt * loader.TILE_BYTES, base, part);
+        else if (part < 2 * ROUNDS) loader.load_round(g_desc, jt * loader.TILE_BYTES, base + Ring::TILE_ELEMS * 2, part - ROUNDS);
+        else if (lane < RPW) {
+            if (part == 2 * ROUNDS)
+                async_load16(a_desc, __builtin_amdgcn_readfirstlane(base + Ring::AUX_OFF + wave * RPW * 16),
+                             (wave * RPW + lane) * 16, jt * BM * 16);
+            else
+                async_load4(p_desc, __builtin_amdgcn_readfirstlane(base + Ring::QPOS_OFF + wave * RPW * 4),
+                            (wave * RPW + lane) * 4, jt * BM * 4);
+        }
+    };
+
+    // ---- d = 128, mask-free tiles: the vector work in the shadow of the matrix instructions --------------------
+    // One wavefront per SIMD: nobody else fills the matrix core while this wavefront runs its exponentials, so the tile is
+    // ordered by hand.  The scores of the first 32 queries are formed as usual; their exponentials, packing and dS then run
+    // between the matrix instructions that form the scores of the other 32 queries, and the vector work of those runs between
+    // the dV / dK products of the first 32.  A group = four matrix instructions (six in the first, which starts the accumulators
+    // with the aux step) and the 14 vector instructions of four score elements, three or four of them after each matrix
+    // instruction; the compiler's scheduler puts the phases one after the other, so the groups are inline assembly on registers
+    // named in the text (scores S0 / P0 / S1 / P1 at v192-v255, packed P and dS of the four 16-query chunks at v160-v191).
+    // The text knows nothing about hazards: dependent matrix instructions are two apart, a group whose vector instructions read
+    // scores that matrix instructions have just written starts with a wait, an exponential is read three or more instructions later.
+#define SCFA_DK_HALF(X0, X1, X2, X3, D0, D1, D2, D3, W0, W1, E0, E1, M0, M1, M2, M3)                                                   \
+    M0 "v_mul_f32 " X0 ", %[c], " X0 "\n\t v_mul_f32 " X1 ", %[c], " X1 "\n\t v_mul_f32 " X2 ", %[c], " X2 "\n\t"                       \
+    M1 "v_mul_f32 " X3 ", %[c], " X3 "\n\t v_exp_f32 " X0 ", " X0 "\n\t v_exp_f32 " X1 ", " X1 "\n\t v_exp_f32 " X2 ", " X2 "\n\t"        \
+    M2 "v_exp_f32 " X3 ", " X3 "\n\t v_cvt_pkrtz_f16_f32 " D0 ", " D0 ", " D1 "\n\t v_cvt_pkrtz_f16_f32 " D2 ", " D2 ", " D3 "\n\t"          \
+    M3 "v_cvt_pkrtz_f16_f32 " W0 ", " X0 ", " X1 "\n\t v_cvt_pkrtz_f16_f32 " W1 ", " X2 ", " X3 "\n\t"                                   \
+    "v_pk_mul_f16 " E0 ", " W0 ", " D0 "\n\t v_pk_mul_f16 " E1 ", " W1 ", " D2 "\n\t"
+#define SCFA_DK_R_S0 "{v[192:207]}"
+#define SCFA_DK_R_P0 "{v[208:223]}"
+#define SCFA_DK_R_S1 "{v[224:239]}"
+#define SCFA_DK_R_P1 "{v[240:255]}"
+#define SCFA_DK_R_PF(c) "{v[" #c "]}"
+    // scores of the second 32 queries, two steps of the head dimension: S1 += Qrow K, P1 += dOrow V
+#define SCFA_DK_M_S                                                                                                                  \
+    "v_mfma_f32_32x32x16_f16 v[224:239], %[f0], %[k0], v[224:239]\n\t", "v_mfma_f32_32x32x16_f16 v[240:255], %[f1], %[v0], v[240:255]\n\t", \
+    "v_mfma_f32_32x32x16_f16 v[224:239], %[f2], %[k1], v[224:239]\n\t", "v_mfma_f32_32x32x16_f16 v[240:255], %[f3], %[v1], v[240:255]\n\t"
+    // dV^T += dO^T P, dK^T += Q^T dS for one 16-query chunk and two 32-wide blocks of the head dimension
+#define SCFA_DK_M_G                                                                                                                  \
+    "v_mfma_f32_32x32x16_f16 %[a0], %[f0], %[pf], %[a0]\n\t", "v_mfma_f32_32x32x16_f16 %[a1], %[f1], %[sf], %[a1]\n\t",                 \
+    "v_mfma_f32_32x32x16_f16 %[a2], %[f2], %[pf], %[a2]\n\t", "v_mfma_f32_32x32x16_f16 %[a3], %[f3], %[sf], %[a3]\n\t"
+#define SCFA_DK_HALF_(...) SCFA_DK_HALF(__VA_ARGS__)
+    const float cexp_u = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, cexp)));
+    auto pin = [&]() __attribute__((always_inline)) { asm volatile("" ::: "memory"); };   // LDS reads stay on their side
+    auto tile_d128 = [&](int buf, auto, int jt_next, int buf_next) __attribute__((always_inline)) {   // generic: only instantiated at d = 128
+        const uint16_t* Qt = q_tile(buf);
+        const uint16_t* Gt = g_tile(buf);
+        const uint16_t* At = aux_tile(buf);
+        f32x16 S0, P0, S1, P1;
+        f16x8 pf0, sf0, pf1, sf1, pf2, sf2, pf3, sf3;
+        // rows of Q and dO for two steps of the head dimension (Q, dO, Q, dO)
+        auto rows2 = [&](f16x8 (&f)[4], int qb, int kk0) __attribute__((always_inline)) {
+            f[0] = swz_rows<D>(Qt, qb * 32 + l32, kk0 * 16 + h * 8);
+            f[1] = swz_rows<D>(Gt, qb * 32 + l32, kk0 * 16 + h * 8);
+            f[2] = swz_rows<D>(Qt, qb * 32 + l32, (kk0 + 1) * 16 + h * 8);
+            f[3] = swz_rows<D>(Gt, qb * 32 + l32, (kk0 + 1) * 16 + h * 8);
+        };
+        // transposed dO and Q fragments of 16-query chunk c4 for head-dimension blocks db0, db0 + 1 (dO, Q, dO, Q)
+        auto trans2 = [&](f16x8 (&f)[4], int c4, int db0) __attribute__((always_inline)) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                int oa, ob;
+                swz_trans_offsets<D>(c4 * 16, (db0 + u) * 32, lane, oa, ob);
+                f[2 * u] = swz_trans(Gt, oa, ob);
+                f[2 * u + 1] = swz_trans(Qt, oa, ob);
+            }
+        };
+        f16x8 fa[4], fb[4];
+        // first 32 queries: aux step, then the head dimension with the row fragments one step ahead
+        {
+            const f16x8 ax = as_f16x8(*reinterpret_cast<const uint4*>(&At[l32 * 8]));
+            S0 = mfma16(ax, sub_lse, zero16());
+            P0 = mfma16(ax, sub_delta, zero16());
+            rows2(fa, 0, 0);
+#pragma unroll
+            for (int g = 0; g < D / 32; ++g) {
+                if (g + 1 < D / 32) { if (g & 1) rows2(fa, 0, 2 * g + 2); else rows2(fb, 0, 2 * g + 2); }
+                else rows2(fa, 1, 0);        // g = 3 uses fb: fa takes the first rows of the other 32 queries
+                __builtin_amdgcn_sched_barrier(0);
+                const f16x8 (&f)[4] = (g & 1) ? fb : fa;
+                S0 = mfma16(f[0], kf[2 * g], S0);
+                P0 = mfma16(f[1], vf[2 * g], P0);
+                S0 = mfma16(f[2], kf[2 * g + 1], S0);
+                P0 = mfma16(f[3], vf[2 * g + 1], P0);
+                issue_part(jt_next, buf_next, 2 * g);        // two of the eight Q and dO rounds per step
+                issue_part(jt_next, buf_next, 2 * g + 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // fa = rows of the other 32 queries, steps 0 and 1
+        const f16x8 ax1 = as_f16x8(*reinterpret_cast<const uint4*>(&At[(32 + l32) * 8]));
+        pin(); rows2(fb, 1, 2); pin();
+        asm volatile("v_mfma_f32_32x32x16_f16 v[224:239], %[ax], %[sl], 0\n\t v_mfma_f32_32x32x16_f16 v[240:255], %[ax], %[sd], 0\n\t s_nop 7\n\t"
+                     SCFA_DK_HALF_("v192", "v193", "v194", "v195", "v208", "v209", "v210", "v211", "v160", "v161", "v164", "v165", SCFA_DK_M_S)
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "=&" SCFA_DK_R_S1(S1), "=&" SCFA_DK_R_P1(P1), "=&{v[160:163]}"(pf0), "=&{v[164:167]}"(sf0)
+                     : [c] "s"(cexp_u), [ax] "v"(ax1), [sl] "v"(sub_lse), [sd] "v"(sub_delta), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]),
+                       [k0] "v"(kf[0]), [v0] "v"(vf[0]), [k1] "v"(kf[1]), [v1] "v"(vf[1]));
+        pin(); rows2(fa, 1, 4); issue_part(jt_next, buf_next, 8); pin();
+        asm volatile(SCFA_DK_HALF_("v196", "v197", "v198", "v199", "v212", "v213", "v214", "v215", "v162", "v163", "v166", "v167", SCFA_DK_M_S)
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[160:163]}"(pf0), "+{v[164:167]}"(sf0)
+                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]),
+                       [k0] "v"(kf[2]), [v0] "v"(vf[2]), [k1] "v"(kf[3]), [v1] "v"(vf[3]));
+        pin(); rows2(fb, 1, 6); issue_part(jt_next, buf_next, 9); pin();
+        asm volatile(SCFA_DK_HALF_("v200", "v201", "v202", "v203", "v216", "v217", "v218", "v219", "v168", "v169", "v172", "v173", SCFA_DK_M_S)
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[168:171]}"(pf1), "=&{v[172:175]}"(sf1)
+                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]),
+                       [k0] "v"(kf[4]), [v0] "v"(vf[4]), [k1] "v"(kf[5]), [v1] "v"(vf[5]));
+        pin(); trans2(fa, 0, 0); pin();
+        asm volatile(SCFA_DK_HALF_("v204", "v205", "v206", "v207", "v220", "v221", "v222", "v223", "v170", "v171", "v174", "v175", SCFA_DK_M_S)
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[168:171]}"(pf1), "+{v[172:175]}"(sf1)
+                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]),
+                       [k0] "v"(kf[6]), [v0] "v"(vf[6]), [k1] "v"(kf[7]), [v1] "v"(vf[7]));
+        // the other 32 queries' vector work under the dV / dK products of the first 16-query chunks
+        pin(); trans2(fb, 0, 2); pin();
+        asm volatile("s_nop 7\n\t"
+                     SCFA_DK_HALF_("v224", "v225", "v226", "v227", "v240", "v241", "v242", "v243", "v176", "v177", "v180", "v181", SCFA_DK_M_G)
+                     : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[176:179]}"(pf2), "=&{v[180:183]}"(sf2),
+                       [a0] "+a"(dvacc[0]), [a1] "+a"(dkacc[0]), [a2] "+a"(dvacc[1]), [a3] "+a"(dkacc[1])
+                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]), [pf] "{v[160:163]}"(pf0), [sf] "{v[164:167]}"(sf0));
+        pin(); trans2(fa, 1, 0); pin();
+        asm volatile(SCFA_DK_HALF_("v228", "v229", "v230", "v231", "v244", "v245", "v246", "v247", "v178", "v179", "v182", "v183", SCFA_DK_M_G)
+                     : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[176:179]}"(pf2), "+{v[180:183]}"(sf2),
+                       [a0] "+a"(dvacc[2]), [a1] "+a"(dkacc[2]), [a2] "+a"(dvacc[3]), [a3] "+a"(dkacc[3])
+                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]), [pf] "{v[160:163]}"(pf0), [sf] "{v[164:167]}"(sf0));
+        pin(); trans2(fb, 1, 2); pin();
+        asm volatile(SCFA_DK_HALF_("v232", "v233", "v234", "v235", "v248", "v249", "v250", "v251", "v184", "v185", "v188", "v189", SCFA_DK_M_G)
+                     : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[184:187]}"(pf3), "=&{v[188:191]}"(sf3),
+                       [a0] "+a"(dvacc[0]), [a1] "+a"(dkacc[0]), [a2] "+a"(dvacc[1]), [a3] "+a"(dkacc[1])
+                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]), [pf] "{v[168:171]}"(pf1), [sf] "{v[172:175]}"(sf1));
+        pin(); trans2(fa, 2, 0); pin();
+        asm volatile(SCFA_DK_HALF_("v236", "v237", "v238", "v239", "v252", "v253", "v254", "v255", "v186", "v187", "v190", "v191", SCFA_DK_M_G)
+                     : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[184:187]}"(pf3), "+{v[188:191]}"(sf3),
+                       [a0] "+a"(dvacc[2]), [a1] "+a"(dkacc[2]), [a2] "+a"(dvacc[3]), [a3] "+a"(dkacc[3])
+                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]), [pf] "{v[168:171]}"(pf1), [sf] "{v[172:175]}"(sf1));
+        // dV / dK products of the last two 16-query chunks, fragments one step ahead
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {       // (chunk 2, blocks 0-1), (chunk 2, blocks 2-3), (chunk 3, 0-1), (chunk 3, 2-3)
+            const int c4 = 2 + (g >> 1), db0 = 2 * (g & 1);
+            if (g + 1 < 4) { if (g & 1) trans2(fa, 2 + ((g + 1) >> 1), 2 * ((g + 1) & 1)); else trans2(fb, 2 + ((g + 1) >> 1), 2 * ((g + 1) & 1)); }
+            __builtin_amdgcn_sched_barrier(0);
+            const f16x8 (&f)[4] = (g & 1) ? fb : fa;
+            const f16x8 pf = c4 == 2 ? pf2 : pf3, sf = c4 == 2 ? sf2 : sf3;
+            acc_mfma16(dvacc[db0], f[0], pf);
+            acc_mfma16(dkacc[db0], f[1], sf);
+            acc_mfma16(dvacc[db0 + 1], f[2], pf);
+            acc_mfma16(dkacc[db0 + 1], f[3], sf);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+
+    auto tile = [&](int buf, auto masked_tag, int jt_next, int buf_next) {
         constexpr bool MASKED = decltype(masked_tag)::value;
+        if constexpr (D == 128 && !MASKED) { tile_d128(buf, masked_tag, jt_next, buf_next); return; }
         const uint16_t* Qt = q_tile(buf);
         const uint16_t* Gt = g_tile(buf);
         const uint16_t* At = aux_tile(buf);
@@ -446,7 +604,8 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         wait_async<LOADS_PER_TILE * (NBUF - 2)>();
         lds_barrier();
         const int refill = cur == 0 ? NBUF - 1 : cur - 1;
-        issue(jt + NBUF - 1, refill);
+        constexpr bool SPREAD = D == 128 && !MASKED;   // the hand-ordered tile issues the loads itself, between its groups
+        if (!SPREAD) issue(jt + NBUF - 1, refill);
         // sort keys ascend along the queries of an item: a tile that lies entirely below or entirely
         // above what may see the keys of this wavefront contributes nothing to it
         bool skip = false;
@@ -455,7 +614,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
             skip = (uint32_t)__builtin_amdgcn_readfirstlane(qpos_tile(cur)[last]) < klo_wave ||
                    (uint32_t)__builtin_amdgcn_readfirstlane(qpos_tile(cur)[0]) > khi_wave;
         }
-        if (!skip) tile(cur, masked_tag);
+        if (!skip) tile(cur, masked_tag, jt + NBUF - 1, refill);
         cur = cur == NBUF - 1 ? 0 : cur + 1;
     };
     int jt = 0;

@@ -252,6 +252,12 @@ struct AsyncTile {
             voff[u] = (row * CH + (slot ^ swz<D>(row))) * 16;  // the chunk that belongs there
         }
     }
+    // one of the ROUNDS loads of a tile, for callers that spread a tile's loads over their own work
+    __device__ __forceinline__ void load_round(u32x4 desc, int tile_byte_offset, uint32_t tile_lds, int u) const
+    {
+        const uint32_t wave_base = tile_lds + ((uint32_t)threadIdx.x >> 6) * 1024u;
+        async_load16(desc, __builtin_amdgcn_readfirstlane(wave_base + (uint32_t)(u * THREADS * 16)), voff[u], tile_byte_offset);
+    }
     // tile_lds: LDS byte address of the tile; tile_byte_offset: wave-uniform offset into the buffer
     __device__ __forceinline__ void load(u32x4 desc, int tile_byte_offset, uint32_t tile_lds) const
     {
