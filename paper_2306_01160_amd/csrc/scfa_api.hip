@@ -129,19 +129,14 @@ static int attn_bwd_impl(const void* q, const void* k, const void* v, const uint
 
     rc = launch_bwd_prep_bf16(o, o_f16, lse, d_o, q_key, qkdrop ? n_q : nullptr, S, T, d, sm_scale, do_perm, delta_perm, lse_perm, aux_perm, amax, inv_scale, st);
     if (rc != SCFA_OK) return rc;
-    // The rows of dropped tokens are zeroed AFTER the pre-pass: its kernels stream dO at the memory's pace, and half a
-    // gigabyte of fresh zeros still on its way out of the caches halves that pace; the matrix-bound kernels that follow do not care.
-    if (qkdrop) {
-        rc = launch_zero_rows(reinterpret_cast<const int32_t*>(q_key), n_q, S, T, d * 4, dq, nullptr, nullptr, 0.f, st);
-        if (rc != SCFA_OK) return rc;
-        rc = launch_zero_rows(reinterpret_cast<const int32_t*>(k_key), n_k, S, T, d * 4, dk, dv, nullptr, 0.f, st);
-        if (rc != SCFA_OK) return rc;
-    }
+    // The rows of dropped tokens (QK-dropping) are zeroed by the two gradient kernels themselves, next to their own stores:
+    // as launches of their own in front of the pre-pass, half a gigabyte of fresh zeros on its way out of the caches halved
+    // the pace of the pre-pass's streaming reads, and anywhere on this stream they would run with nothing beside them.
     rc = launch_attn_bwd_dkdv_bf16(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, d,
-                                   sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, st);
+                                   sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dk, dv, qkdrop ? n_k : nullptr, st);
     if (rc != SCFA_OK) return rc;
     return launch_attn_bwd_dq_bf16(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd,
-                                   S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dq, st);
+                                   S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, dq, qkdrop ? n_q : nullptr, st);
 }
 
 }  // namespace scfa

@@ -239,6 +239,26 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
 // ===========================================================================
 // LDS ring of the dK/dV kernel: Q tile, dO tile, aux rows (three fp16 pieces of LSE log2 e and of D
 // per query) and query positions per buffer, filled asynchronously NBUF - 1 tiles ahead
+// QK-dropping: the rows of dropped tokens get zero gradients.  Entries n_keep .. T of a segment's compacted index vector
+// are the dropped positions; workgroup `w` of the `n_wg` workgroups that serve the segment zeroes the fp32 rows
+// n_keep + w R, + 1, ..., then n_wg R further (R = rows one pass of the workgroup covers), in up to two tensors.  Done by
+// the gradient kernels themselves, after their own stores (or at once, by workgroups without work): the zeros then
+// leave for memory while other workgroups compute, instead of in launches of their own in front of the kernels.
+template <int D>
+__device__ __forceinline__ void zero_dropped_rows(const uint32_t* __restrict__ key_seg, int n_keep, int T, int w, int n_wg,
+                                                  float* __restrict__ out0, float* __restrict__ out1, size_t seg)
+{
+    constexpr int CPR = D / 4;            // 16-byte chunks of an fp32 row
+    constexpr int R = 256 / CPR;          // rows per pass of the workgroup
+    const int sub = (int)threadIdx.x / CPR, c = (int)threadIdx.x % CPR;
+    const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (long long r = (long long)n_keep + (long long)w * R + sub; r < T; r += (long long)n_wg * R) {
+        const size_t row = (seg + (key_seg[r] & KEY_POS_MASK)) * D;
+        reinterpret_cast<float4*>(out0 + row)[c] = z;
+        if (out1) reinterpret_cast<float4*>(out1 + row)[c] = z;
+    }
+}
+
 template <int D>
 struct DkdvRing {
     static constexpr int BM = BWD_TILE_M;
@@ -256,7 +276,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const float* __restrict__ inv_scale,
     const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
-    float* __restrict__ dk, float* __restrict__ dv)
+    float* __restrict__ dk, float* __restrict__ dv, const int32_t* __restrict__ n_keep_k)
 {
     constexpr int BM = BWD_TILE_M;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -275,10 +295,14 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
     const int k_begin = it[BW_KBEGIN], k_count = it[BW_KCOUNT];
     const int q_begin = it[BW_QBEGIN], q_count = it[BW_QCOUNT], q_masked = it[BW_QMASKED];
-    if (k_count <= 0) return;
+    if (k_count <= 0) {   // no work: only the share of the dropped rows (n_keep_k: QK-dropping, else null)
+        if (n_keep_k) zero_dropped_rows<D>(k_key + (size_t)s * T, n_keep_k[s], T, w, n_work, dk, dv, (size_t)s * T);
+        return;
+    }
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
+    if (n_keep_k) zero_dropped_rows<D>(k_key + seg, n_keep_k[s], T, w, n_work, dk, dv, seg);
     const float cexp = tau * LOG2E;   // scores are raw <q, k> sums minus LSE in the same units: P = 2^(cexp x)
     const int krow = wave * 32 + l32;
     const bool kvalid = krow < k_count;
@@ -644,7 +668,7 @@ template <int D>
 static int launch_dkdv_t(const void* q, const void* k, const void* v, const void* do_perm,
                          const void* aux_perm, const float* inv_scale,
                          const uint32_t* q_key, const uint32_t* k_key, const int32_t* work, int n_work, int S,
-                         int T, float tau, int strict, float* dk, float* dv, hipStream_t st)
+                         int T, float tau, int strict, float* dk, float* dv, const int32_t* n_keep_k, hipStream_t st)
 {
     const size_t smem = (size_t)DkdvRing<D>::NBUF * DkdvRing<D>::BUF_BYTES;
     static std::atomic<unsigned long long> lds_allowed{0};
@@ -652,7 +676,7 @@ static int launch_dkdv_t(const void* q, const void* k, const void* v, const void
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dkdv_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, (const uint16_t*)aux_perm, inv_scale, q_key, k_key,
-                       work, n_work, S, T, tau, strict, dk, dv);
+                       work, n_work, S, T, tau, strict, dk, dv, n_keep_k);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -675,13 +699,14 @@ int occupancy_attn_bwd_dkdv_bf16(int d, int* out)
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
                               const uint32_t* q_key, const uint32_t* k_key, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, float tau, int strict, float* dk, float* dv, hipStream_t st)
+                              int S, int T, int d, float tau, int strict, float* dk, float* dv, const int32_t* n_keep_k,
+                              hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DKDV, st);
     if (d == 64)
-        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, tau, strict, dk, dv, st);
+        return launch_dkdv_t<64>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, tau, strict, dk, dv, n_keep_k, st);
     if (d == 128)
-        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, tau, strict, dk, dv, st);
+        return launch_dkdv_t<128>(q, k, v, do_perm, aux_perm, inv_scale, q_key, k_key, bwd_work, n_bwd, S, T, tau, strict, dk, dv, n_keep_k, st);
     return SCFA_EUNSUPPORTED;
 }
 
@@ -709,7 +734,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     const uint16_t* __restrict__ do_perm, const float* __restrict__ lse_perm,
     const float* __restrict__ delta_perm, const float* __restrict__ inv_scale,
     const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
-    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict, float* __restrict__ dq)
+    const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict, float* __restrict__ dq,
+    const int32_t* __restrict__ n_keep_q)
 {
     constexpr int BN = FWD_TILE_N;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
@@ -726,10 +752,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
     const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
     const int q_begin = it[W_QBEGIN], q_count = it[W_QCOUNT];
     const int k_begin = it[W_KBEGIN], k_count = it[W_KCOUNT], k_nomask = it[W_KNOMASK];
-    if (q_count <= 0) return;
+    if (q_count <= 0) {   // no work: only the share of the dropped rows (n_keep_q: QK-dropping, else null)
+        if (n_keep_q) zero_dropped_rows<D>(q_key + (size_t)s * T, n_keep_q[s], T, w, n_work, dq, nullptr, (size_t)s * T);
+        return;
+    }
 
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
+    if (n_keep_q) zero_dropped_rows<D>(q_key + seg, n_keep_q[s], T, w, n_work, dq, nullptr, seg);
     const int qrow = wave * 32 + l32;
     const bool qvalid = qrow < q_count;
     const int qr = min(qrow, q_count - 1);              // rows past the end repeat the last one; never written
@@ -948,7 +978,7 @@ template <int D>
 static int launch_dq_t(const void* q, const void* k, const void* v, const void* do_perm,
                        const float* lse_perm, const float* delta_perm, const float* inv_scale,
                        const uint32_t* q_key, const uint32_t* k_key, const int32_t* work, int n_work, int S, int T,
-                       float tau, int strict, float* dq, hipStream_t st)
+                       float tau, int strict, float* dq, const int32_t* n_keep_q, hipStream_t st)
 {
     const size_t smem = (size_t)DqRing<D>::NBUF * DqRing<D>::BUF_BYTES;
     static std::atomic<unsigned long long> lds_allowed{0};
@@ -956,7 +986,7 @@ static int launch_dq_t(const void* q, const void* k, const void* v, const void* 
     dim3 grid((unsigned)((size_t)S * n_work)), block(256);
     hipLaunchKernelGGL(attn_bwd_dq_f16_kernel<D>, grid, block, smem, st, (const uint16_t*)q, (const uint16_t*)k,
                        (const uint16_t*)v, (const uint16_t*)do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key,
-                       work, n_work, S, T, tau, strict, dq);
+                       work, n_work, S, T, tau, strict, dq, n_keep_q);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -979,13 +1009,13 @@ int occupancy_attn_bwd_dq_bf16(int d, int* out)
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
                             const uint32_t* q_key, const uint32_t* k_key, const int32_t* fwd_work, int n_fwd,
-                            int S, int T, int d, float tau, int strict, float* dq, hipStream_t st)
+                            int S, int T, int d, float tau, int strict, float* dq, const int32_t* n_keep_q, hipStream_t st)
 {
     ProfScope prof(SCFA_K_BWD_DQ, st);
     if (d == 64)
-        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd, S, T, tau, strict, dq, st);
+        return launch_dq_t<64>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd, S, T, tau, strict, dq, n_keep_q, st);
     if (d == 128)
-        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd, S, T, tau, strict, dq, st);
+        return launch_dq_t<128>(q, k, v, do_perm, lse_perm, delta_perm, inv_scale, q_key, k_key, fwd_work, n_fwd, S, T, tau, strict, dq, n_keep_q, st);
     return SCFA_EUNSUPPORTED;
 }
 

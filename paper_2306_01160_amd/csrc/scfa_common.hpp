@@ -106,11 +106,12 @@ int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, con
 int launch_attn_bwd_dkdv_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                               const void* aux_perm, const float* inv_scale,
                               const uint32_t* q_key, const uint32_t* k_key, const int32_t* bwd_work, int n_bwd,
-                              int S, int T, int d, float tau, int strict, float* dk, float* dv, hipStream_t st);
+                              int S, int T, int d, float tau, int strict, float* dk, float* dv, const int32_t* n_keep_k,
+                              hipStream_t st);
 int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const void* do_perm,
                             const float* lse_perm, const float* delta_perm, const float* inv_scale,
                             const uint32_t* q_key, const uint32_t* k_key, const int32_t* fwd_work, int n_fwd,
-                            int S, int T, int d, float tau, int strict, float* dq, hipStream_t st);
+                            int S, int T, int d, float tau, int strict, float* dq, const int32_t* n_keep_q, hipStream_t st);
 
 int occupancy_attn_fwd_bf16(int d, int* out);
 int occupancy_attn_bwd_dkdv_bf16(int d, int* out);

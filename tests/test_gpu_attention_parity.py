@@ -240,12 +240,13 @@ def test_first_kept_query_before_first_kept_key():
     assert_within(errs, wl.dtype)
 
 
-def test_outputs_do_not_depend_on_previous_buffer_contents():
-    """Outputs are fully written: poison-filled output buffers give the same result."""
+@pytest.mark.parametrize("T,d,pq,pk", [(500, 64, 0.5, 0.5), (1300, 128, 0.3, 0.7), (2100, 64, 0.9, 0.1)])
+def test_outputs_do_not_depend_on_previous_buffer_contents(T, d, pq, pk):
+    """Outputs are fully written, the rows of dropped tokens included: poison-filled output buffers give the same result."""
     from paper_2306_01160_amd import binding as sc
     from gpu_util import to_gpu
     from paper_2306_01160_amd import pipeline
-    wl = W.qkdrop_bernoulli(44, 1, 2, 500, 64, 0.5, 0.5)
+    wl = W.qkdrop_bernoulli(44, 1, 2, T, d, pq, pk)
     q, k, v, do, lq, lk = to_gpu(wl)
     o1, lse1, ctx = pipeline.qkdrop_forward(q, k, v, lq, lk, wl.tau)
     g1 = pipeline.qkdrop_backward(ctx, do)
@@ -258,6 +259,9 @@ def test_outputs_do_not_depend_on_previous_buffer_contents():
     assert torch.equal(o1, o2) and torch.equal(lse1, lse2)
     for a, b in zip(g1, g2):
         assert torch.equal(a, b)
+    for g, lab in ((g2[0], lq), (g2[1], lk), (g2[2], lk)):
+        assert not g.reshape(-1, d)[lab.reshape(-1) == 0].any()
+    assert not o2.reshape(-1, d)[lq.reshape(-1) == 0].any()
 
 
 def test_two_runs_are_bit_identical():
