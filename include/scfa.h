@@ -95,11 +95,13 @@ const char *scfa_error_string(int code);
  *                      along r.  The hash-sparse attention entry points take these: "same
  *                      bucket and position <= p" is one range test on them.
  *   ws, ws_bytes       (nullable) device scratch of scfa_sort_workspace_bytes(S, T, nb)
- *                      bytes, 4-byte aligned, contents undefined afterwards.  With it, long
+ *                      bytes, 4-byte aligned, contents undefined afterwards.  Long
  *                      sequences (T >= 8192) in few segments are cut into chunks that
- *                      several workgroups sort (a counting kernel runs first); without it,
- *                      or when it is too small, one workgroup sorts a segment.  The
- *                      outputs are the same bits either way.
+ *                      several workgroups sort.  Up to T = 16384 every workgroup counts
+ *                      the keys of the other chunks itself and the scratch is not touched;
+ *                      beyond that a counting kernel runs first and writes its counters
+ *                      here, and without the scratch, or when it is too small, one
+ *                      workgroup sorts a segment.  The outputs are the same bits either way.
  * Limits: 1 <= nb <= SCFA_MAX_BUCKETS, 1 <= T, 1 <= S.
  */
 size_t scfa_sort_workspace_bytes(int S, int T, int nb);   /* also for the compaction (any nb) */

@@ -45,7 +45,11 @@ constexpr int SORT_PREFETCH = 16;  // 64-token steps whose keys are loaded toget
 // segment can be cut into n_chunks runs of chunk_len tokens (a multiple of 64 * SORT_WAVES), one
 // workgroup each: a first kernel counts the keys of every chunk, the sort kernel then starts each
 // key of its chunk after all smaller keys of the segment and after the same key in earlier chunks.
+// Up to SELF_COUNT_MAX_T tokens per segment the first kernel is not launched: every workgroup of the
+// sort kernel counts the keys of the other chunks itself (at most 16 more keys per thread, read from
+// L2), which costs less than a launch.
 constexpr int COUNT_THREADS = 256;
+constexpr int SELF_COUNT_MAX_T = 16384;
 
 template <bool KEEP_MODE>
 __global__ __launch_bounds__(COUNT_THREADS) void sort_chunk_count_kernel(
@@ -74,6 +78,8 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
     int32_t* hist = smem;                       // [SORT_WAVES][nb]  counts, then running bases
     int32_t* tot = smem + SORT_WAVES * nb;      // [nb+1]
     int32_t* before = tot + nb + 1;             // [nb] tokens of the key in earlier chunks of the segment
+    int32_t* later = before + nb;               // [nb] ... in later chunks (only when this kernel counts them itself)
+    const bool self_count = n_chunks > 1 && chunk_counts == nullptr;
     const int chunk = blockIdx.x % n_chunks;
     const int ps = blockIdx.x / n_chunks;
     const bool second = ps >= S;
@@ -95,7 +101,23 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
     const int r1 = min(r0 + run, c1);
 
     for (int i = threadIdx.x; i < SORT_WAVES * nb; i += SORT_THREADS) hist[i] = 0;
+    if (self_count)
+        for (int i = threadIdx.x; i < nb; i += SORT_THREADS) { before[i] = 0; later[i] = 0; }
     __syncthreads();
+    if (self_count) {   // the other chunks of the segment: [0, c0) and [c1, T), eight keys per thread in flight
+        const int n_other = c0 + (T - c1);
+        for (int i0 = threadIdx.x; i0 < n_other; i0 += 8 * SORT_THREADS) {
+            int kv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * SORT_THREADS;
+                kv[u] = i < n_other ? load_key<KEEP_MODE>(keys, seg + (i < c0 ? i : i - c0 + c1), nb) : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u)
+                if (kv[u] >= 0) atomicAdd(i0 + u * SORT_THREADS < c0 ? &before[kv[u]] : &later[kv[u]], 1);
+        }
+    }
     // histogram of the run; the keys of SORT_PREFETCH 64-token steps are loaded together so
     // that the memory latency is paid once per group, not once per step.  A run of at most
     // one group (T <= 16 * 64 * SORT_PREFETCH) keeps its keys in registers for the ranking.
@@ -122,7 +144,10 @@ __global__ __launch_bounds__(SORT_THREADS) void stable_sort_small_keys_kernel(
             acc += c;
         }
         int earlier = 0;
-        if (n_chunks > 1) {   // the segment's total and the part of it that lies in earlier chunks
+        if (self_count) {
+            earlier = before[k];
+            acc += earlier + later[k];
+        } else if (n_chunks > 1) {   // the segment's total and the part of it that lies in earlier chunks
             const int32_t* cc = chunk_counts + (size_t)ps * n_chunks * nb + k;
             acc = 0;
             for (int c = 0; c < n_chunks; ++c) {
@@ -220,19 +245,21 @@ size_t sort_workspace_bytes(int n_problems, int S, int T, int nb)
 
 template <bool KEEP_MODE>
 static int launch_sort_t(int kid, int n_problems, const SortProblem& p0, const SortProblem& p1, int S, int T, int nb,
-                         int nbits, void* ws, size_t ws_bytes, hipStream_t st, bool timed = true)
+                         int nbits, void* ws, size_t ws_bytes, hipStream_t st, bool timed = true,
+                         bool self_count_ok = true)
 {
-    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + 2 * (size_t)nb + 1);
+    const size_t smem = sizeof(int32_t) * ((size_t)SORT_WAVES * nb + 3 * (size_t)nb + 1);
     int n_chunks = sort_chunks(S * n_problems, T);
-    if (!ws || ws_bytes < sort_workspace_bytes(n_problems, S, T, nb)) n_chunks = 1;   // no scratch: one workgroup per segment
+    const bool self_count = self_count_ok && T <= SELF_COUNT_MAX_T;   // the sort kernel counts the other chunks itself
+    if (!self_count && (!ws || ws_bytes < sort_workspace_bytes(n_problems, S, T, nb))) n_chunks = 1;   // no scratch: one workgroup per segment
     int chunk_len = sort_chunk_len(T, n_chunks);
     n_chunks = (T + chunk_len - 1) / chunk_len;      // rounding the length up may leave fewer chunks
     ProfScope prof(timed ? kid : -1, st);            // the timers create events: not on the allocation-free path
-    if (n_chunks > 1)
+    if (n_chunks > 1 && !self_count)
         hipLaunchKernelGGL(sort_chunk_count_kernel<KEEP_MODE>, dim3(S * n_problems * n_chunks), dim3(COUNT_THREADS),
                            sizeof(int32_t) * nb, st, p0.keys, p1.keys, S, T, nb, n_chunks, chunk_len, (int32_t*)ws);
     hipLaunchKernelGGL(stable_sort_small_keys_kernel<KEEP_MODE>, dim3(S * n_problems * n_chunks), dim3(SORT_THREADS), smem,
-                       st, p0, p1, S, T, nb, nbits, n_chunks, chunk_len, (const int32_t*)ws);
+                       st, p0, p1, S, T, nb, nbits, n_chunks, chunk_len, self_count ? nullptr : (const int32_t*)ws);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -292,7 +319,7 @@ int launch_sort_by_bucket_static(const int32_t* bucket, int S, int T, int nb, in
     const SortProblem p0{bucket, idx, sorted, off, key}, p1{nullptr, nullptr, nullptr, nullptr, nullptr};
     // every counter the sort kernel reads is written by the counting kernel of the same call, so
     // what an earlier call left in the array does not matter
-    return launch_sort_t<false>(SCFA_K_SORT, 1, p0, p1, S, T, nb, nbits, ptr, SCFA_STATIC_SCRATCH_BYTES, st, false);
+    return launch_sort_t<false>(SCFA_K_SORT, 1, p0, p1, S, T, nb, nbits, ptr, SCFA_STATIC_SCRATCH_BYTES, st, false, false);
 }
 
 int launch_compact_keep(int n_problems, const uint8_t* keep0, const uint8_t* keep1, int S, int T, int32_t* idx0,

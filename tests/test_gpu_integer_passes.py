@@ -180,10 +180,12 @@ def test_pair_entry_points_match_single_calls(S, T, nb):
             assert torch.equal(g_k[s_, :b], r_k[s_, :b]) and torch.equal(g_v[s_, :b], r_v[s_, :b])
 
 
-@pytest.mark.parametrize("S,T,nb", [(1, 65536, 16), (3, 20000, 256), (2, 8192, 1), (1, 32768 + 77, 7), (40, 8192, 8)])
+@pytest.mark.parametrize("S,T,nb", [(1, 65536, 16), (3, 20000, 256), (2, 8192, 1), (1, 32768 + 77, 7), (40, 8192, 8),
+                                    (5, 16384, 33), (3, 12000, 5), (2, 16385, 9)])
 def test_chunked_sort_equals_single_workgroup_sort(S, T, nb):
-    """Long sequences are cut into chunks sorted by several workgroups when scratch is given: same
-    bits as the one-workgroup-per-segment kernel and as the oracle, for the sort and the compaction."""
+    """Long sequences are cut into chunks sorted by several workgroups (above 16384 tokens only when scratch
+    is given; up to there every workgroup counts the other chunks itself): same bits with and without
+    scratch and as the oracle, for the sort and the compaction."""
     rng = np.random.default_rng(S * 7 + T + nb)
     b = rng.integers(0, nb, (S, T)).astype(np.int32)
     b[0, : T // 3] = nb - 1                          # a long run of one key across chunk borders
