@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     float* __restrict__ dk, float* __restrict__ dv, const int32_t* __restrict__ n_keep_k)
 {
     constexpr int BM = BWD_TILE_M;
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    extern __shared__ __attribute__((aligned(256))) unsigned char smem_raw[];   // the hand-ordered d = 128 tile XORs address bits below 256
     using Ring = DkdvRing<D>;
     constexpr int NBUF = Ring::NBUF, BUF_BYTES = Ring::BUF_BYTES;
     constexpr int RPW = BM / 4;                                               // aux rows / positions loaded per wavefront
@@ -300,7 +300,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
         return;
     }
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
     if (n_keep_k) zero_dropped_rows<D>(k_key + seg, n_keep_k[s], T, w, n_work, dk, dv, seg);
     const float cexp = tau * LOG2E;   // scores are raw <q, k> sums minus LSE in the same units: P = 2^(cexp x)
@@ -404,12 +404,36 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     // named in the text (scores S0 / P0 / S1 / P1 at v192-v255, packed P and dS of the four 16-query chunks at v160-v191).
     // The text knows nothing about hazards: dependent matrix instructions are two apart, a group whose vector instructions read
     // scores that matrix instructions have just written starts with a wait, an exponential is read three or more instructions later.
-#define SCFA_DK_HALF(X0, X1, X2, X3, D0, D1, D2, D3, W0, W1, E0, E1, M0, M1, M2, M3)                                                   \
-    M0 "v_mul_f32 " X0 ", %[c], " X0 "\n\t v_mul_f32 " X1 ", %[c], " X1 "\n\t v_mul_f32 " X2 ", %[c], " X2 "\n\t"                       \
-    M1 "v_mul_f32 " X3 ", %[c], " X3 "\n\t v_exp_f32 " X0 ", " X0 "\n\t v_exp_f32 " X1 ", " X1 "\n\t v_exp_f32 " X2 ", " X2 "\n\t"        \
+#define SCFA_DK_HALF(X0, X1, X2, X3, D0, D1, D2, D3, W0, W1, E0, E1, M0, M1, M2, M3, L0, L1)                                           \
+    M0 L0 "v_mul_f32 " X0 ", %[c], " X0 "\n\t v_mul_f32 " X1 ", %[c], " X1 "\n\t v_mul_f32 " X2 ", %[c], " X2 "\n\t"                    \
+    M1 L1 "v_mul_f32 " X3 ", %[c], " X3 "\n\t v_exp_f32 " X0 ", " X0 "\n\t v_exp_f32 " X1 ", " X1 "\n\t v_exp_f32 " X2 ", " X2 "\n\t"     \
     M2 "v_exp_f32 " X3 ", " X3 "\n\t v_cvt_pkrtz_f16_f32 " D0 ", " D0 ", " D1 "\n\t v_cvt_pkrtz_f16_f32 " D2 ", " D2 ", " D3 "\n\t"          \
     M3 "v_cvt_pkrtz_f16_f32 " W0 ", " X0 ", " X1 "\n\t v_cvt_pkrtz_f16_f32 " W1 ", " X2 ", " X3 "\n\t"                                   \
-    "v_pk_mul_f16 " E0 ", " W0 ", " D0 "\n\t v_pk_mul_f16 " E1 ", " W1 ", " D2 "\n\t"
+    "v_pk_mul_f16 " E0 ", " W0 ", " D0 "\n\t v_pk_mul_f16 " E1 ", " W1 ", " D2 "\n\t s_waitcnt lgkmcnt(0)\n\t"
+    // The LDS reads of the NEXT group's fragments ride in the text too (L0 after the first, L1 after the second matrix instruction;
+    // the group ends with their wait, which they have met by then): issued by the compiler between the groups they were a burst of
+    // four to eight reads during which no matrix instruction could be issued.  Fragment sets fa / fb live at v128-v143 / v144-v159.
+    // Rows of Q and dO (other 32 queries) for two steps of the head dimension: %[ra] addresses the even step, ^ 32 bytes the odd one;
+    // dO tiles lie 16384 bytes behind Q tiles.
+#define SCFA_DK_L_ROWS(F0, F1, F2, F3)                                                                                                  \
+    "ds_read_b128 " F0 ", %[ra]\n\t ds_read_b128 " F1 ", %[ra] offset:16384\n\t",                                                     \
+    "v_xor_b32 %[t0], 32, %[ra]\n\t ds_read_b128 " F2 ", %[t0]\n\t ds_read_b128 " F3 ", %[t0] offset:16384\n\t"
+    // Transposed dO and Q fragments of one 16-query chunk (byte offsets OG, OQ of the chunk in the dO and Q tiles) for two 32-wide blocks
+    // of the head dimension: %[ta], %[tb] address the two reads of the even block, ^ 64 bytes those of the odd one.
+#define SCFA_DK_L_TRANS(F0L, F0H, F1L, F1H, F2L, F2H, F3L, F3H, OG, OQ)                                                                  \
+    "ds_read_b64_tr_b16 " F0L ", %[ta] offset:" OG "\n\t ds_read_b64_tr_b16 " F0H ", %[tb] offset:" OG "\n\t"                          \
+    "ds_read_b64_tr_b16 " F1L ", %[ta] offset:" OQ "\n\t ds_read_b64_tr_b16 " F1H ", %[tb] offset:" OQ "\n\t",                         \
+    "v_xor_b32 %[t0], 64, %[ta]\n\t v_xor_b32 %[t1], 64, %[tb]\n\t"                                                                  \
+    "ds_read_b64_tr_b16 " F2L ", %[t0] offset:" OG "\n\t ds_read_b64_tr_b16 " F2H ", %[t1] offset:" OG "\n\t"                          \
+    "ds_read_b64_tr_b16 " F3L ", %[t0] offset:" OQ "\n\t ds_read_b64_tr_b16 " F3H ", %[t1] offset:" OQ "\n\t"
+#define SCFA_DK_L_ROWS_(...) SCFA_DK_L_ROWS(__VA_ARGS__)
+#define SCFA_DK_L_TRANS_(...) SCFA_DK_L_TRANS(__VA_ARGS__)
+#define SCFA_FA_ROWS "v[128:131]", "v[132:135]", "v[136:139]", "v[140:143]"
+#define SCFA_FB_ROWS "v[144:147]", "v[148:151]", "v[152:155]", "v[156:159]"
+#define SCFA_FA_PAIRS "v[128:129]", "v[130:131]", "v[132:133]", "v[134:135]", "v[136:137]", "v[138:139]", "v[140:141]", "v[142:143]"
+#define SCFA_FB_PAIRS "v[144:145]", "v[146:147]", "v[148:149]", "v[150:151]", "v[152:153]", "v[154:155]", "v[156:157]", "v[158:159]"
+#define SCFA_FA_OUT "=&{v[128:131]}"(fa[0]), "=&{v[132:135]}"(fa[1]), "=&{v[136:139]}"(fa[2]), "=&{v[140:143]}"(fa[3])
+#define SCFA_FB_OUT "=&{v[144:147]}"(fb[0]), "=&{v[148:151]}"(fb[1]), "=&{v[152:155]}"(fb[2]), "=&{v[156:159]}"(fb[3])
 #define SCFA_DK_R_S0 "{v[192:207]}"
 #define SCFA_DK_R_P0 "{v[208:223]}"
 #define SCFA_DK_R_S1 "{v[224:239]}"
@@ -439,95 +463,137 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
             f[2] = swz_rows<D>(Qt, qb * 32 + l32, (kk0 + 1) * 16 + h * 8);
             f[3] = swz_rows<D>(Gt, qb * 32 + l32, (kk0 + 1) * 16 + h * 8);
         };
-        // transposed dO and Q fragments of 16-query chunk c4 for head-dimension blocks db0, db0 + 1 (dO, Q, dO, Q)
-        auto trans2 = [&](f16x8 (&f)[4], int c4, int db0) __attribute__((always_inline)) {
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                int oa, ob;
-                swz_trans_offsets<D>(c4 * 16, (db0 + u) * 32, lane, oa, ob);
-                f[2 * u] = swz_trans(Gt, oa, ob);
-                f[2 * u + 1] = swz_trans(Qt, oa, ob);
-            }
-        };
-        f16x8 fa[4], fb[4];
+        f16x8 fa[4], fb[4], ax1;
         // first 32 queries: aux step, then the head dimension with the row fragments one step ahead
         {
             const f16x8 ax = as_f16x8(*reinterpret_cast<const uint4*>(&At[l32 * 8]));
             S0 = mfma16(ax, sub_lse, zero16());
             P0 = mfma16(ax, sub_delta, zero16());
             rows2(fa, 0, 0);
+            // one LDS read (and every other time one asynchronous load) after each matrix instruction: a burst of four
+            // reads and two loads between groups of four matrix instructions lets the matrix core run dry.  The last group
+            // requests the first rows of the other 32 queries before its matrix instructions: the next stage starts with them.
 #pragma unroll
             for (int g = 0; g < D / 32; ++g) {
-                if (g + 1 < D / 32) { if (g & 1) rows2(fa, 0, 2 * g + 2); else rows2(fb, 0, 2 * g + 2); }
-                else rows2(fa, 1, 0);        // g = 3 uses fb: fa takes the first rows of the other 32 queries
-                __builtin_amdgcn_sched_barrier(0);
                 const f16x8 (&f)[4] = (g & 1) ? fb : fa;
+                f16x8 (&n)[4] = (g & 1) ? fa : fb;
+                const bool last = g + 1 == D / 32;
+                const int nqb = last ? 1 : 0, nkk = last ? 0 : 2 * g + 2;
+                __builtin_amdgcn_sched_barrier(0);
+                if (last) {
+                    n[0] = swz_rows<D>(Qt, nqb * 32 + l32, nkk * 16 + h * 8);
+                    n[1] = swz_rows<D>(Gt, nqb * 32 + l32, nkk * 16 + h * 8);
+                    n[2] = swz_rows<D>(Qt, nqb * 32 + l32, (nkk + 1) * 16 + h * 8);
+                    n[3] = swz_rows<D>(Gt, nqb * 32 + l32, (nkk + 1) * 16 + h * 8);
+                    ax1 = as_f16x8(*reinterpret_cast<const uint4*>(&At[(32 + l32) * 8]));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
                 S0 = mfma16(f[0], kf[2 * g], S0);
-                P0 = mfma16(f[1], vf[2 * g], P0);
-                S0 = mfma16(f[2], kf[2 * g + 1], S0);
-                P0 = mfma16(f[3], vf[2 * g + 1], P0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!last) n[0] = swz_rows<D>(Qt, nqb * 32 + l32, nkk * 16 + h * 8);
                 issue_part(jt_next, buf_next, 2 * g);        // two of the eight Q and dO rounds per step
+                __builtin_amdgcn_sched_barrier(0);
+                P0 = mfma16(f[1], vf[2 * g], P0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!last) n[1] = swz_rows<D>(Gt, nqb * 32 + l32, nkk * 16 + h * 8);
+                __builtin_amdgcn_sched_barrier(0);
+                S0 = mfma16(f[2], kf[2 * g + 1], S0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!last) n[2] = swz_rows<D>(Qt, nqb * 32 + l32, (nkk + 1) * 16 + h * 8);
                 issue_part(jt_next, buf_next, 2 * g + 1);
+                __builtin_amdgcn_sched_barrier(0);
+                P0 = mfma16(f[3], vf[2 * g + 1], P0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (!last) n[3] = swz_rows<D>(Gt, nqb * 32 + l32, (nkk + 1) * 16 + h * 8);
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
         // fa = rows of the other 32 queries, steps 0 and 1
-        const f16x8 ax1 = as_f16x8(*reinterpret_cast<const uint4*>(&At[(32 + l32) * 8]));
-        pin(); rows2(fb, 1, 2); pin();
+        // byte addresses inside LDS (the tile ring is 256-byte aligned, so head-dimension steps and blocks are XORs of address bits)
+        static_assert(D != 128 || (Ring::TILE_ELEMS * 2 == 16384 && BUF_BYTES % 256 == 0), "offsets written into the assembly text");
+        const uint32_t rb = lds_address(Qt) + 2u * (uint32_t)swz_offset<D>(32 + l32, h * 8);
+        int oa0, ob0;
+        swz_trans_offsets<D>(0, 0, lane, oa0, ob0);
+        const uint32_t ta = lds_address(Qt) + 2u * (uint32_t)oa0, tb = lds_address(Qt) + 2u * (uint32_t)ob0;
+        uint32_t t0, t1;
         asm volatile("v_mfma_f32_32x32x16_f16 v[224:239], %[ax], %[sl], 0\n\t v_mfma_f32_32x32x16_f16 v[240:255], %[ax], %[sd], 0\n\t s_nop 7\n\t"
-                     SCFA_DK_HALF_("v192", "v193", "v194", "v195", "v208", "v209", "v210", "v211", "v160", "v161", "v164", "v165", SCFA_DK_M_S)
-                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "=&" SCFA_DK_R_S1(S1), "=&" SCFA_DK_R_P1(P1), "=&{v[160:163]}"(pf0), "=&{v[164:167]}"(sf0)
+                     SCFA_DK_HALF_("v192", "v193", "v194", "v195", "v208", "v209", "v210", "v211", "v160", "v161", "v164", "v165", SCFA_DK_M_S, SCFA_DK_L_ROWS_(SCFA_FB_ROWS))
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "=&" SCFA_DK_R_S1(S1), "=&" SCFA_DK_R_P1(P1), "=&{v[160:163]}"(pf0), "=&{v[164:167]}"(sf0),
+                       SCFA_FB_OUT, [t0] "=&v"(t0)
                      : [c] "s"(cexp_u), [ax] "v"(ax1), [sl] "v"(sub_lse), [sd] "v"(sub_delta), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]),
-                       [k0] "v"(kf[0]), [v0] "v"(vf[0]), [k1] "v"(kf[1]), [v1] "v"(vf[1]));
-        pin(); rows2(fa, 1, 4); issue_part(jt_next, buf_next, 8); pin();
-        asm volatile(SCFA_DK_HALF_("v196", "v197", "v198", "v199", "v212", "v213", "v214", "v215", "v162", "v163", "v166", "v167", SCFA_DK_M_S)
-                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[160:163]}"(pf0), "+{v[164:167]}"(sf0)
+                       [k0] "v"(kf[0]), [v0] "v"(vf[0]), [k1] "v"(kf[1]), [v1] "v"(vf[1]), [ra] "v"(rb ^ 64u));
+        pin(); issue_part(jt_next, buf_next, 8); pin();
+        asm volatile(SCFA_DK_HALF_("v196", "v197", "v198", "v199", "v212", "v213", "v214", "v215", "v162", "v163", "v166", "v167", SCFA_DK_M_S, SCFA_DK_L_ROWS_(SCFA_FA_ROWS))
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[160:163]}"(pf0), "+{v[164:167]}"(sf0),
+                       SCFA_FA_OUT, [t0] "=&v"(t0)
                      : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]),
-                       [k0] "v"(kf[2]), [v0] "v"(vf[2]), [k1] "v"(kf[3]), [v1] "v"(vf[3]));
-        pin(); rows2(fb, 1, 6); issue_part(jt_next, buf_next, 9); pin();
-        asm volatile(SCFA_DK_HALF_("v200", "v201", "v202", "v203", "v216", "v217", "v218", "v219", "v168", "v169", "v172", "v173", SCFA_DK_M_S)
-                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[168:171]}"(pf1), "=&{v[172:175]}"(sf1)
+                       [k0] "v"(kf[2]), [v0] "v"(vf[2]), [k1] "v"(kf[3]), [v1] "v"(vf[3]), [ra] "v"(rb ^ 128u));
+        pin(); issue_part(jt_next, buf_next, 9); pin();
+        asm volatile(SCFA_DK_HALF_("v200", "v201", "v202", "v203", "v216", "v217", "v218", "v219", "v168", "v169", "v172", "v173", SCFA_DK_M_S, SCFA_DK_L_ROWS_(SCFA_FB_ROWS))
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[168:171]}"(pf1), "=&{v[172:175]}"(sf1),
+                       SCFA_FB_OUT, [t0] "=&v"(t0)
                      : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]),
-                       [k0] "v"(kf[4]), [v0] "v"(vf[4]), [k1] "v"(kf[5]), [v1] "v"(vf[5]));
-        pin(); trans2(fa, 0, 0); pin();
-        asm volatile(SCFA_DK_HALF_("v204", "v205", "v206", "v207", "v220", "v221", "v222", "v223", "v170", "v171", "v174", "v175", SCFA_DK_M_S)
-                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[168:171]}"(pf1), "+{v[172:175]}"(sf1)
+                       [k0] "v"(kf[4]), [v0] "v"(vf[4]), [k1] "v"(kf[5]), [v1] "v"(vf[5]), [ra] "v"(rb ^ 192u));
+        asm volatile(SCFA_DK_HALF_("v204", "v205", "v206", "v207", "v220", "v221", "v222", "v223", "v170", "v171", "v174", "v175", SCFA_DK_M_S,
+                                   SCFA_DK_L_TRANS_(SCFA_FA_PAIRS, "16384", "0"))
+                     : "+" SCFA_DK_R_S0(S0), "+" SCFA_DK_R_P0(P0), "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[168:171]}"(pf1), "+{v[172:175]}"(sf1),
+                       SCFA_FA_OUT, [t0] "=&v"(t0), [t1] "=&v"(t1)
                      : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]),
-                       [k0] "v"(kf[6]), [v0] "v"(vf[6]), [k1] "v"(kf[7]), [v1] "v"(vf[7]));
+                       [k0] "v"(kf[6]), [v0] "v"(vf[6]), [k1] "v"(kf[7]), [v1] "v"(vf[7]), [ta] "v"(ta), [tb] "v"(tb));
         // the other 32 queries' vector work under the dV / dK products of the first 16-query chunks
-        pin(); trans2(fb, 0, 2); pin();
         asm volatile("s_nop 7\n\t"
-                     SCFA_DK_HALF_("v224", "v225", "v226", "v227", "v240", "v241", "v242", "v243", "v176", "v177", "v180", "v181", SCFA_DK_M_G)
+                     SCFA_DK_HALF_("v224", "v225", "v226", "v227", "v240", "v241", "v242", "v243", "v176", "v177", "v180", "v181", SCFA_DK_M_G,
+                                   SCFA_DK_L_TRANS_(SCFA_FB_PAIRS, "16384", "0"))
                      : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[176:179]}"(pf2), "=&{v[180:183]}"(sf2),
-                       [a0] "+a"(dvacc[0]), [a1] "+a"(dkacc[0]), [a2] "+a"(dvacc[1]), [a3] "+a"(dkacc[1])
-                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]), [pf] "{v[160:163]}"(pf0), [sf] "{v[164:167]}"(sf0));
-        pin(); trans2(fa, 1, 0); pin();
-        asm volatile(SCFA_DK_HALF_("v228", "v229", "v230", "v231", "v244", "v245", "v246", "v247", "v178", "v179", "v182", "v183", SCFA_DK_M_G)
+                       [a0] "+a"(dvacc[0]), [a1] "+a"(dkacc[0]), [a2] "+a"(dvacc[1]), [a3] "+a"(dkacc[1]), SCFA_FB_OUT, [t0] "=&v"(t0), [t1] "=&v"(t1)
+                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]), [pf] "{v[160:163]}"(pf0), [sf] "{v[164:167]}"(sf0),
+                       [ta] "v"(ta ^ 128u), [tb] "v"(tb ^ 128u));
+        asm volatile(SCFA_DK_HALF_("v228", "v229", "v230", "v231", "v244", "v245", "v246", "v247", "v178", "v179", "v182", "v183", SCFA_DK_M_G,
+                                   SCFA_DK_L_TRANS_(SCFA_FA_PAIRS, "20480", "4096"))
                      : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[176:179]}"(pf2), "+{v[180:183]}"(sf2),
-                       [a0] "+a"(dvacc[2]), [a1] "+a"(dkacc[2]), [a2] "+a"(dvacc[3]), [a3] "+a"(dkacc[3])
-                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]), [pf] "{v[160:163]}"(pf0), [sf] "{v[164:167]}"(sf0));
-        pin(); trans2(fb, 1, 2); pin();
-        asm volatile(SCFA_DK_HALF_("v232", "v233", "v234", "v235", "v248", "v249", "v250", "v251", "v184", "v185", "v188", "v189", SCFA_DK_M_G)
+                       [a0] "+a"(dvacc[2]), [a1] "+a"(dkacc[2]), [a2] "+a"(dvacc[3]), [a3] "+a"(dkacc[3]), SCFA_FA_OUT, [t0] "=&v"(t0), [t1] "=&v"(t1)
+                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]), [pf] "{v[160:163]}"(pf0), [sf] "{v[164:167]}"(sf0),
+                       [ta] "v"(ta), [tb] "v"(tb));
+        asm volatile(SCFA_DK_HALF_("v232", "v233", "v234", "v235", "v248", "v249", "v250", "v251", "v184", "v185", "v188", "v189", SCFA_DK_M_G,
+                                   SCFA_DK_L_TRANS_(SCFA_FB_PAIRS, "20480", "4096"))
                      : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "=&{v[184:187]}"(pf3), "=&{v[188:191]}"(sf3),
-                       [a0] "+a"(dvacc[0]), [a1] "+a"(dkacc[0]), [a2] "+a"(dvacc[1]), [a3] "+a"(dkacc[1])
-                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]), [pf] "{v[168:171]}"(pf1), [sf] "{v[172:175]}"(sf1));
-        pin(); trans2(fa, 2, 0); pin();
-        asm volatile(SCFA_DK_HALF_("v236", "v237", "v238", "v239", "v252", "v253", "v254", "v255", "v186", "v187", "v190", "v191", SCFA_DK_M_G)
+                       [a0] "+a"(dvacc[0]), [a1] "+a"(dkacc[0]), [a2] "+a"(dvacc[1]), [a3] "+a"(dkacc[1]), SCFA_FB_OUT, [t0] "=&v"(t0), [t1] "=&v"(t1)
+                     : [c] "s"(cexp_u), [f0] "v"(fa[0]), [f1] "v"(fa[1]), [f2] "v"(fa[2]), [f3] "v"(fa[3]), [pf] "{v[168:171]}"(pf1), [sf] "{v[172:175]}"(sf1),
+                       [ta] "v"(ta ^ 128u), [tb] "v"(tb ^ 128u));
+        asm volatile(SCFA_DK_HALF_("v236", "v237", "v238", "v239", "v252", "v253", "v254", "v255", "v186", "v187", "v190", "v191", SCFA_DK_M_G,
+                                   SCFA_DK_L_TRANS_(SCFA_FA_PAIRS, "24576", "8192"))
                      : "+" SCFA_DK_R_S1(S1), "+" SCFA_DK_R_P1(P1), "+{v[184:187]}"(pf3), "+{v[188:191]}"(sf3),
-                       [a0] "+a"(dvacc[2]), [a1] "+a"(dkacc[2]), [a2] "+a"(dvacc[3]), [a3] "+a"(dkacc[3])
-                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]), [pf] "{v[168:171]}"(pf1), [sf] "{v[172:175]}"(sf1));
+                       [a0] "+a"(dvacc[2]), [a1] "+a"(dkacc[2]), [a2] "+a"(dvacc[3]), [a3] "+a"(dkacc[3]), SCFA_FA_OUT, [t0] "=&v"(t0), [t1] "=&v"(t1)
+                     : [c] "s"(cexp_u), [f0] "v"(fb[0]), [f1] "v"(fb[1]), [f2] "v"(fb[2]), [f3] "v"(fb[3]), [pf] "{v[168:171]}"(pf1), [sf] "{v[172:175]}"(sf1),
+                       [ta] "v"(ta), [tb] "v"(tb));
         // dV / dK products of the last two 16-query chunks, fragments one step ahead
 #pragma unroll
         for (int g = 0; g < 4; ++g) {       // (chunk 2, blocks 0-1), (chunk 2, blocks 2-3), (chunk 3, 0-1), (chunk 3, 2-3)
             const int c4 = 2 + (g >> 1), db0 = 2 * (g & 1);
-            if (g + 1 < 4) { if (g & 1) trans2(fa, 2 + ((g + 1) >> 1), 2 * ((g + 1) & 1)); else trans2(fb, 2 + ((g + 1) >> 1), 2 * ((g + 1) & 1)); }
-            __builtin_amdgcn_sched_barrier(0);
+            const int nc4 = 2 + ((g + 1) >> 1), ndb0 = 2 * ((g + 1) & 1);
+            const bool more = g + 1 < 4;
             const f16x8 (&f)[4] = (g & 1) ? fb : fa;
+            f16x8 (&n)[4] = (g & 1) ? fa : fb;
             const f16x8 pf = c4 == 2 ? pf2 : pf3, sf = c4 == 2 ? sf2 : sf3;
+            int oa0, ob0, oa1, ob1;
+            swz_trans_offsets<D>(nc4 * 16, ndb0 * 32, lane, oa0, ob0);
+            swz_trans_offsets<D>(nc4 * 16, (ndb0 + 1) * 32, lane, oa1, ob1);
+            __builtin_amdgcn_sched_barrier(0);
             acc_mfma16(dvacc[db0], f[0], pf);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) n[0] = swz_trans(Gt, oa0, ob0);
+            __builtin_amdgcn_sched_barrier(0);
             acc_mfma16(dkacc[db0], f[1], sf);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) n[1] = swz_trans(Qt, oa0, ob0);
+            __builtin_amdgcn_sched_barrier(0);
             acc_mfma16(dvacc[db0 + 1], f[2], pf);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) n[2] = swz_trans(Gt, oa1, ob1);
+            __builtin_amdgcn_sched_barrier(0);
             acc_mfma16(dkacc[db0 + 1], f[3], sf);
+            __builtin_amdgcn_sched_barrier(0);
+            if (more) n[3] = swz_trans(Qt, oa1, ob1);
             __builtin_amdgcn_sched_barrier(0);
         }
     };
@@ -645,8 +711,7 @@ __global__ __launch_bounds__(256) void attn_bwd_dkdv_f16_kernel(
     for (; jt < n_masked; ++jt) step(jt, std::true_type{});
     for (; jt < n_tiles; ++jt) step(jt, std::false_type{});
     wait_async<0>();   // nothing may still be landing in LDS when the wavefront ends
-    if (D == 128) acc_mfma_drain();
-
+    if constexpr (D == 128) acc_mfma_drain(dvacc[0], dvacc[1], dvacc[2], dvacc[3], dkacc[0], dkacc[1], dkacc[2], dkacc[3]);
     if (kvalid) {
         const float us = inv_scale[s];
         const float sk = tau * us;   // dK = tau dS^T Q
@@ -757,7 +822,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void a
         return;
     }
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
     if (n_keep_q) zero_dropped_rows<D>(q_key + seg, n_keep_q[s], T, w, n_work, dq, nullptr, seg);
     const int qrow = wave * 32 + l32;
@@ -1020,3 +1085,4 @@ int launch_attn_bwd_dq_bf16(const void* q, const void* k, const void* v, const v
 }
 
 }  // namespace scfa
+

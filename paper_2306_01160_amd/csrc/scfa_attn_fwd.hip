@@ -94,7 +94,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(D == 64
     const int k_begin = it[W_KBEGIN], k_count = it[W_KCOUNT], k_nomask = it[W_KNOMASK];
     if (q_count <= 0) return;
 
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63, l32 = lane & 31, h = lane >> 5;
+    const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, h = lane >> 5;
     const size_t seg = (size_t)s * T;
 
     int qrow[QB], qpos[QB];

@@ -43,9 +43,12 @@ __device__ __forceinline__ void acc_mfma16(f32x16& acc, f16x8 a, f16x8 b)
 {
     asm("s_nop 1\n\tv_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
-__device__ __forceinline__ void acc_mfma_drain()
+// The wait takes the accumulators as operands: every later read of them then depends on it.  (Without them the
+// compiler is free to read an accumulator that this statement does not mention before the wait.)
+__device__ __forceinline__ void acc_mfma_drain(f32x16& a0, f32x16& a1, f32x16& a2, f32x16& a3, f32x16& a4, f32x16& a5, f32x16& a6,
+                                               f32x16& a7)
 {
-    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    asm volatile("s_nop 15\n\ts_nop 15" : "+a"(a0), "+a"(a1), "+a"(a2), "+a"(a3), "+a"(a4), "+a"(a5), "+a"(a6), "+a"(a7)::"memory");
 }
 
 __device__ __forceinline__ f32x16 zero16()
@@ -242,9 +245,12 @@ struct AsyncTile {
     static constexpr int TILE_BYTES = ROWS * D * 2;
     static_assert(ROWS * CH % THREADS == 0, "tile must split evenly over the workgroup");
     int voff[ROUNDS];
+    uint32_t wave_off;   // where this wavefront's kilobyte of a round starts: kept in a scalar register, so that the LDS address
+                         // of a load (M0) is scalar arithmetic and not a vector add read back with v_readfirstlane per load
 
     __device__ __forceinline__ void init()
     {
+        wave_off = __builtin_amdgcn_readfirstlane(((uint32_t)threadIdx.x >> 6) * 1024u);
 #pragma unroll
         for (int u = 0; u < ROUNDS; ++u) {
             const int pos = u * THREADS + (int)threadIdx.x;   // LDS chunk position this lane fills
@@ -255,17 +261,14 @@ struct AsyncTile {
     // one of the ROUNDS loads of a tile, for callers that spread a tile's loads over their own work
     __device__ __forceinline__ void load_round(u32x4 desc, int tile_byte_offset, uint32_t tile_lds, int u) const
     {
-        const uint32_t wave_base = tile_lds + ((uint32_t)threadIdx.x >> 6) * 1024u;
-        async_load16(desc, __builtin_amdgcn_readfirstlane(wave_base + (uint32_t)(u * THREADS * 16)), voff[u], tile_byte_offset);
+        async_load16(desc, tile_lds + wave_off + (uint32_t)(u * THREADS * 16), voff[u], tile_byte_offset);
     }
     // tile_lds: LDS byte address of the tile; tile_byte_offset: wave-uniform offset into the buffer
     __device__ __forceinline__ void load(u32x4 desc, int tile_byte_offset, uint32_t tile_lds) const
     {
-        const uint32_t wave_base = tile_lds + ((uint32_t)threadIdx.x >> 6) * 1024u;
 #pragma unroll
         for (int u = 0; u < ROUNDS; ++u)
-            async_load16(desc, __builtin_amdgcn_readfirstlane(wave_base + (uint32_t)(u * THREADS * 16)), voff[u],
-                         tile_byte_offset);
+            async_load16(desc, tile_lds + wave_off + (uint32_t)(u * THREADS * 16), voff[u], tile_byte_offset);
     }
 };
 
