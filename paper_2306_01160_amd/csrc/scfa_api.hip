@@ -85,15 +85,17 @@ static int attn_fwd_impl(const void* q, const void* k, const void* v, const uint
     if (o_f16 && (dtype != SCFA_BF16 || !aligned16(o_f16))) return SCFA_EINVAL;
     const int S = B * H;
     const int esize = dtype == SCFA_BF16 ? 2 : 4;
-    if (qkdrop) {
-        rc = launch_zero_rows(reinterpret_cast<const int32_t*>(q_key), n_q, S, T, d * esize, o, nullptr, lse, -INFINITY, st);
-        if (rc != SCFA_OK) return rc;
-    }
-    if (dtype == SCFA_F32)
+    if (dtype == SCFA_F32) {
+        if (qkdrop) {   // rows of dropped queries: zeros, LSE = -inf
+            rc = launch_zero_rows(reinterpret_cast<const int32_t*>(q_key), n_q, S, T, d * esize, o, nullptr, lse, -INFINITY, st);
+            if (rc != SCFA_OK) return rc;
+        }
         return launch_attn_fwd_f32((const float*)q, (const float*)k, (const float*)v, q_key, k_key, work,
                                    n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, (float*)o, lse, st);
+    }
+    // bf16: the forward kernel writes the rows of dropped queries itself
     return launch_attn_fwd_bf16(q, k, v, q_key, k_key, work, n_work, S, T, d, sm_scale, flags & SCFA_FLAG_STRICT_CAUSAL, o,
-                                lse, o_f16, st);
+                                lse, o_f16, qkdrop ? n_q : nullptr, st);
 }
 
 static int attn_bwd_impl(const void* q, const void* k, const void* v, const uint32_t* q_key,

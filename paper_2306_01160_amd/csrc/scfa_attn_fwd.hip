@@ -62,12 +62,28 @@ struct FwdRing {
     static constexpr int NBUF = D == 64 ? 3 : 2;
 };
 
+// QK-dropping: the output rows of dropped queries are zeros and their LSE is -inf.  Every workgroup of the forward kernel, the
+// ones without work included, writes a strided share of its segment's dropped rows next to its own stores (a launch of its own
+// for them ran with nothing beside it).  key_seg: the segment's query index vector, dropped positions from n_keep on.
+template <int D, int THREADS>
+__device__ __forceinline__ void fill_dropped_rows(const uint32_t* __restrict__ key_seg, int n_keep, int T, int w, int n_wg,
+                                                  uint16_t* __restrict__ o, float* __restrict__ lse, size_t seg)
+{
+    constexpr int CPR = D / 8, R = THREADS / CPR;   // 16-byte pieces per bf16 row, rows per pass
+    const int sub = (int)threadIdx.x / CPR, c = (int)threadIdx.x % CPR;
+    for (long long r = (long long)n_keep + (long long)w * R + sub; r < T; r += (long long)n_wg * R) {
+        const size_t pos = seg + (key_seg[r] & KEY_POS_MASK);
+        reinterpret_cast<uint4*>(o + pos * D)[c] = make_uint4(0u, 0u, 0u, 0u);
+        if (c == 0) lse[pos] = -INFINITY;
+    }
+}
+
 template <int D, int NW, int QB>
 __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(D == 64 ? 3 : 2))) void attn_fwd_f16_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint32_t* __restrict__ q_key, const uint32_t* __restrict__ k_key,
     const int32_t* __restrict__ work, int n_work, int S, int T, float tau, int strict,
-    uint16_t* __restrict__ o, float* __restrict__ lse, uint16_t* __restrict__ o_f16)
+    uint16_t* __restrict__ o, float* __restrict__ lse, uint16_t* __restrict__ o_f16, const int32_t* __restrict__ n_keep_q)
 {
     static_assert(NW * QB * 32 == FWD_TILE_M, "workgroup must cover the forward query tile");
     const float cexp = tau * LOG2E;   // scores are raw <q, k> sums; the exponent of every probability is cexp * (sum - m)
@@ -92,6 +108,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(D == 64
     const int32_t* it = work + ((size_t)s * n_work + w) * WORK_STRIDE;
     const int q_begin = it[W_QBEGIN], q_count = it[W_QCOUNT];
     const int k_begin = it[W_KBEGIN], k_count = it[W_KCOUNT], k_nomask = it[W_KNOMASK];
+    if (n_keep_q) fill_dropped_rows<D, THREADS>(q_key + (size_t)s * T, n_keep_q[s], T, w, n_work, o, lse, (size_t)s * T);
     if (q_count <= 0) return;
 
     const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, l32 = lane & 31, h = lane >> 5;
@@ -420,7 +437,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(D == 64
 template <int D, int NW, int QB>
 static int launch_fwd_t(const void* q, const void* k, const void* v, const uint32_t* q_key, const uint32_t* k_key,
                         const int32_t* work, int n_work, int S, int T, float tau, int strict, void* o,
-                        float* lse, void* o_f16, hipStream_t st)
+                        float* lse, void* o_f16, const int32_t* n_keep_q, hipStream_t st)
 {
     constexpr size_t smem = (size_t)FwdRing<D>::NBUF * FwdRing<D>::BUF_BYTES;
     static std::atomic<unsigned long long> lds_allowed{0};
@@ -428,7 +445,7 @@ static int launch_fwd_t(const void* q, const void* k, const void* v, const uint3
     dim3 grid((unsigned)((size_t)S * n_work));
     hipLaunchKernelGGL((attn_fwd_f16_kernel<D, NW, QB>), grid, dim3(NW * 64), smem, st, (const uint16_t*)q,
                        (const uint16_t*)k, (const uint16_t*)v, q_key, k_key, work, n_work, S, T, tau,
-                       strict, (uint16_t*)o, lse, (uint16_t*)o_f16);
+                       strict, (uint16_t*)o, lse, (uint16_t*)o_f16, n_keep_q);
     SCFA_HIP_TRY(hipGetLastError());
     return SCFA_OK;
 }
@@ -453,11 +470,11 @@ int occupancy_attn_fwd_bf16(int d, int* out)
 
 int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const uint32_t* q_key,
                          const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
-                         float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st)
+                         float tau, int strict, void* o, float* lse, void* o_f16, const int32_t* n_keep_q, hipStream_t st)
 {
     ProfScope prof(SCFA_K_FWD, st);
-    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_key, k_key, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
-    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_key, k_key, work, n_work, S, T, tau, strict, o, lse, o_f16, st);
+    if (d == 64) return launch_fwd_t<64, 4, 1>(q, k, v, q_key, k_key, work, n_work, S, T, tau, strict, o, lse, o_f16, n_keep_q, st);
+    if (d == 128) return launch_fwd_t<128, 4, 1>(q, k, v, q_key, k_key, work, n_work, S, T, tau, strict, o, lse, o_f16, n_keep_q, st);
     return SCFA_EUNSUPPORTED;
 }
 

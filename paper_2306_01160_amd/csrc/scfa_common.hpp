@@ -98,7 +98,8 @@ int launch_attn_fwd_f32(const float* q, const float* k, const float* v, const ui
                         float tau, int strict, float* o, float* lse, hipStream_t st);
 int launch_attn_fwd_bf16(const void* q, const void* k, const void* v, const uint32_t* q_key,
                          const uint32_t* k_key, const int32_t* work, int n_work, int S, int T, int d,
-                         float tau, int strict, void* o, float* lse, void* o_f16, hipStream_t st);
+                         float tau, int strict, void* o, float* lse, void* o_f16, const int32_t* n_keep_q,
+                         hipStream_t st);   // n_keep_q: QK-dropping (the kernel writes the dropped rows), else null
 int launch_bwd_prep_bf16(const void* o, const void* o_f16, const float* lse, const void* d_o, const uint32_t* q_key,
                          const int32_t* n_q,
                          int S, int T, int d, float tau, void* do_perm, float* delta_perm, float* lse_perm,
