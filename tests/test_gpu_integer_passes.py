@@ -215,7 +215,9 @@ def test_chunked_sort_equals_single_workgroup_sort(S, T, nb):
 
 @pytest.mark.parametrize("S,H,T,d,nb,dtype", [(4, 2, 1000, 64, 8, torch.bfloat16), (3, 3, 777, 128, 16, torch.bfloat16),
                                                (2, 1, 4096, 64, 2, torch.bfloat16), (2, 2, 513, 64, 64, torch.float32),
-                                               (1, 1, 1, 64, 4, torch.bfloat16), (2, 2, 300, 128, 256, torch.float32)])
+                                               (1, 1, 1, 64, 4, torch.bfloat16), (2, 2, 300, 128, 256, torch.float32),
+                                               (2, 2, 5000, 64, 64, torch.bfloat16), (3, 1, 70001, 64, 6, torch.bfloat16),
+                                               (2, 2, 2500, 128, 64, torch.bfloat16), (2, 1, 700, 64, 66, torch.bfloat16)])
 def test_lsh_buckets_against_oracle(S, H, T, d, nb, dtype):
     """argmax over [xR, -xR]: an integer decided by floating point.  The kernel decides in fp32, the
     oracle in fp64, so: wherever the oracle's two largest candidates are further apart than fp32
